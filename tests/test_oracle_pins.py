@@ -1,0 +1,360 @@
+"""Pins for the CPU oracle: it is checked against hand-derived values, closed forms,
+library routines on special cases, brute force of a different code shape, and invariants —
+never against itself and never against the HIP path. CPU only."""
+import json
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import ref
+from paper_2605_17889_amd import synth
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _load(name):
+    with open(os.path.join(GOLD, name)) as fh:
+        return json.load(fh)
+
+
+def _bf16_bits_from_float(a):
+    """float array whose values are bf16-exact -> uint16 raw bits (asserts exactness)."""
+    a32 = np.asarray(a, np.float32)
+    bits = (a32.view(np.uint32) >> 16).astype(np.uint16)
+    back = (bits.astype(np.uint32) << 16).view(np.float32)
+    assert np.array_equal(back, a32), "fixture value is not bf16-exact"
+    return bits
+
+
+def _bf16_to_f64(bits):
+    return (bits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
+def _hx(s):
+    return float.fromhex(s) if isinstance(s, str) and "x" in s else float(s)
+
+
+# --------------------------------------------------------------------------- router logits
+@pytest.mark.parametrize("case", _load("route_tree_cases.json")["cases"], ids=lambda c: c["name"])
+def test_logit_tree_hand_cases(case):
+    d, E = case["d"], case["E"]
+    x = np.zeros((1, d), np.float32)
+    for i, v in case["x"].items():
+        x[0, int(i)] = _hx(v)
+    w = np.full((d, E), _hx(case["w_default"]), np.float32)
+    for key, v in case["w"].items():
+        if "," in key:
+            i, e = (int(s) for s in key.split(","))
+        else:
+            i, e = int(key), 0
+        w[i, e] = _hx(v)
+    bias = None if case["bias"] is None else np.array([_hx(b) for b in case["bias"]], np.float32)
+    got = ref.logits(_bf16_bits_from_float(x), w, bias)
+    want = np.array([_hx(v) for v in case["expected"]], np.float32)
+    assert np.array_equal(got[0].view(np.uint32), want.view(np.uint32)), (got, want)
+
+
+def test_logits_exact_on_small_integers():
+    """When every product and partial sum is an exactly representable integer, any correct
+    summation returns the exact dot product; compare with an int64 matmul."""
+    rng = np.random.default_rng(11)
+    T, d, E = 5, 1024, 7
+    xi = rng.integers(-8, 9, size=(T, d))
+    wi = rng.integers(-16, 17, size=(d, E))
+    got = ref.logits(_bf16_bits_from_float(xi.astype(np.float32)), wi.astype(np.float32))
+    assert np.array_equal(got.astype(np.int64), xi @ wi)
+
+
+def test_logits_within_fp32_bound_of_double():
+    """The canonical fp32 logit stays within the standard forward error bound
+    (d * 2^-24 * sum|x_i w_i|) of the double-precision dot product from numpy."""
+    cfg = synth.PRESETS["tiny"]
+    x = synth.bf16_bits(synth.make_tokens(cfg))
+    w = synth.make_router(cfg).numpy()
+    got = ref.logits(x, w)
+    xd = _bf16_to_f64(x)
+    exact = xd @ w.astype(np.float64)
+    bound = cfg.d_model * 2.0 ** -24 * (np.abs(xd) @ np.abs(w.astype(np.float64)))
+    assert np.all(np.abs(got - exact) <= bound)
+    assert np.max(np.abs(got - exact)) > 0          # it really is an fp32 sum, not the double one
+    assert np.allclose(ref.logits_f64(x, w), exact, rtol=1e-13, atol=1e-13)
+
+
+# --------------------------------------------------------------------------------- top-k
+@pytest.mark.parametrize("case", _load("topk_cases.json")["cases"], ids=lambda c: c["name"])
+def test_topk_hand_cases(case):
+    lg = np.array([[float(v) for v in case["logits"]]], np.float32)
+    idx, g = ref.topk(lg, case["k"])
+    assert idx[0].tolist() == case["idx"]
+    assert abs(float(g[0].sum()) - 1.0) <= 1e-6
+    if "gates" in case:
+        assert np.allclose(g[0], case["gates"], atol=2e-7)
+
+
+def test_topk_equals_full_sort_and_gate_identities():
+    """Brute force: a full stable sort of (-logit, index) gives the same order; for k = 2 the
+    gates have the closed form sigmoid(l0 - l1); softmax over all experts followed by
+    renormalisation over the selected ones equals the softmax over the selected logits."""
+    rng = np.random.default_rng(5)
+    T, E = 400, 8
+    lg = rng.normal(0, 1.5, size=(T, E)).astype(np.float32)
+    lg[::7, 3] = lg[::7, 5]                      # plant exact ties
+    lg[::11] = np.round(lg[::11])                # and many more
+    for k in (1, 2, 3, 8):
+        idx, g = ref.topk(lg, k)
+        order = np.argsort(-lg.astype(np.float64), axis=1, kind="stable")[:, :k]
+        assert np.array_equal(idx, order)
+        assert np.all(np.abs(g.sum(1) - 1) <= 1e-6)
+        full = np.exp(lg.astype(np.float64) - lg.max(1, keepdims=True))
+        full /= full.sum(1, keepdims=True)
+        sel = np.take_along_axis(full, idx.astype(np.int64), 1)
+        sel /= sel.sum(1, keepdims=True)
+        assert np.allclose(g, sel, atol=1e-7)
+        if k == E:
+            assert np.array_equal(np.sort(idx, 1), np.tile(np.arange(E), (T, 1)))
+        if k == 2:
+            l0 = np.take_along_axis(lg, idx[:, :1].astype(np.int64), 1)[:, 0].astype(np.float64)
+            l1 = np.take_along_axis(lg, idx[:, 1:].astype(np.int64), 1)[:, 0].astype(np.float64)
+            assert np.allclose(g[:, 0], 1 / (1 + np.exp(l1 - l0)), atol=1e-7)
+
+
+# ----------------------------------------------------------------------------- permutation
+def test_permute_worked_example():
+    c = _load("permute_worked_example.json")
+    counts, offsets, perm, inv = ref.permute(np.array(c["topk_idx"], np.int32), c["E"])
+    assert counts.tolist() == c["counts"] and offsets.tolist() == c["offsets"]
+    assert perm.tolist() == c["perm"] and inv.tolist() == c["inv_perm"]
+
+
+@pytest.mark.parametrize("T,E,k,seed", [(1, 4, 1, 0), (37, 8, 2, 1), (1000, 64, 6, 2), (513, 3, 3, 3)])
+def test_permute_matches_stable_sort_and_invariants(T, E, k, seed):
+    rng = np.random.default_rng(seed)
+    idx = np.stack([rng.permutation(E)[:k] for _ in range(T)]).astype(np.int32)
+    if E > 2:
+        idx[idx == 2] = 1 if k == 1 else idx[idx == 2]      # k=1: leave expert 2 empty
+    counts, offsets, perm, inv = ref.permute(idx, E)
+    flat = idx.reshape(-1)
+    R = T * k
+    assert counts.sum() == R                                  # sum of counts = T*k
+    assert np.array_equal(counts, np.bincount(flat, minlength=E))
+    assert offsets[0] == 0 and offsets[-1] == R and np.array_equal(np.diff(offsets), counts)
+    assert np.array_equal(perm, np.argsort(flat, kind="stable"))   # library routine
+    assert np.array_equal(perm[inv], np.arange(R)) and np.array_equal(inv[perm], np.arange(R))
+    e_sorted = flat[perm]
+    assert np.all(np.diff(e_sorted) >= 0)
+    same = np.diff(e_sorted) == 0
+    assert np.all(np.diff(perm)[same] > 0)                    # stability inside a group
+
+
+def test_gather_is_row_copy():
+    rng = np.random.default_rng(9)
+    x = rng.integers(0, 65536, size=(6, 16)).astype(np.uint16)
+    perm = np.array([3, 0, 5, 11, 7, 1, 2, 4, 6, 8, 9, 10], np.int32)
+    got = ref.gather(x, perm, 2)
+    assert np.array_equal(got, x[perm // 2])
+
+
+# ------------------------------------------------------------------------------ expert FFN
+def test_ffn_worked_example_by_hand():
+    c = _load("ffn_worked_example.json")
+    assert abs(c["silu_1"] - 1 / (1 + math.exp(-1))) < 1e-16
+    xb = _bf16_bits_from_float(np.array([c["x"]], np.float32))
+    W1 = _bf16_bits_from_float(np.array([c["W1"]], np.float32))
+    W3 = _bf16_bits_from_float(np.array([c["W3"]], np.float32))
+    W2 = _bf16_bits_from_float(np.array([c["W2"]], np.float32))
+    y, h = ref.expert_ffn(xb, np.array([0, 1], np.int32), W1, W3, W2, want_h=True)
+    assert np.allclose(h[0], [2 * c["silu_1"], 0.0], rtol=1e-15, atol=0)
+    assert np.allclose(y[0], c["o"], rtol=1e-15)
+
+
+def test_ffn_scalar_closed_form():
+    for xv, w1, w3, w2 in [(1.5, -2.0, 0.5, 3.0), (-0.75, 1.25, -4.0, 0.125), (0.0, 1.0, 1.0, 1.0)]:
+        b = lambda v: _bf16_bits_from_float(np.array(v, np.float32).reshape(1, 1, 1))
+        y = ref.expert_ffn(b(xv).reshape(1, 1), np.array([0, 1], np.int32), b(w1), b(w3), b(w2))
+        a = w1 * xv
+        want = w2 * (a / (1 + math.exp(-a))) * (w3 * xv)
+        assert y.shape == (1, 1) and abs(y[0, 0] - want) <= 1e-15 * max(1.0, abs(want))
+
+
+def test_ffn_identity_weights_closed_form():
+    """f = d and W1 = W3 = W2 = I  =>  y = SiLU(x) * x elementwise."""
+    d = 24
+    rng = np.random.default_rng(2)
+    xb = _bf16_bits_from_float(torch.tensor(rng.normal(size=(5, d))).bfloat16().float().numpy())
+    eye = _bf16_bits_from_float(np.eye(d, dtype=np.float32)[None])
+    y = ref.expert_ffn(xb, np.array([0, 5], np.int32), eye, eye, eye)
+    xv = _bf16_to_f64(xb)
+    assert np.allclose(y, xv / (1 + np.exp(-xv)) * xv, rtol=1e-14, atol=1e-300)
+
+
+def _rand_bits(rng, shape, std):
+    return synth.bf16_bits(torch.tensor(rng.normal(0, std, size=shape), dtype=torch.float32).bfloat16())
+
+
+def test_single_expert_is_three_library_matmuls():
+    """E = 1, k = 1 is a plain SwiGLU MLP: three numpy matmuls with non-square, asymmetric
+    weights (catches a transposed operand or swapped W1/W3/W2)."""
+    rng = np.random.default_rng(3)
+    T, d, f = 9, 512, 96
+    x = _rand_bits(rng, (T, d), 1.0)
+    W1, W3, W2 = _rand_bits(rng, (1, f, d), 0.05), _rand_bits(rng, (1, f, d), 0.05), _rand_bits(rng, (1, d, f), 0.05)
+    wr = rng.normal(0, 0.02, size=(d, 1)).astype(np.float32)
+    y, idx, g = ref.layer_tokens(x, wr, None, W1, W3, W2, 1)
+    assert np.all(idx == 0) and np.all(g == 1.0)
+    xd = _bf16_to_f64(x)
+    a = xd @ _bf16_to_f64(W1[0]).T
+    b = xd @ _bf16_to_f64(W3[0]).T
+    want = (a / (1 + np.exp(-a)) * b) @ _bf16_to_f64(W2[0]).T
+    assert np.allclose(y, want, rtol=1e-12, atol=1e-14)
+
+
+def _dense_bruteforce(x, lg, W1, W3, W2, k):
+    """Per-token dense evaluation: run ALL experts, weight them with a dense gate vector that
+    is the softmax over all E logits, zeroed off the top-k and renormalised."""
+    T, d = x.shape
+    E = W1.shape[0]
+    xd = _bf16_to_f64(x)
+    y = np.zeros((T, d))
+    for t in range(T):
+        l = lg[t].astype(np.float64)
+        order = sorted(range(E), key=lambda e: (-l[e], e))[:k]
+        p = np.exp(l - l.max())
+        p /= p.sum()
+        dense = np.zeros(E)
+        dense[order] = p[order]
+        dense /= dense.sum()
+        for e in range(E):
+            a = _bf16_to_f64(W1[e]) @ xd[t]
+            b = _bf16_to_f64(W3[e]) @ xd[t]
+            y[t] += dense[e] * (_bf16_to_f64(W2[e]) @ (a / (1 + np.exp(-a)) * b))
+    return y
+
+
+@pytest.mark.parametrize("E,k", [(8, 2), (5, 3), (4, 4)])
+def test_layer_equals_dense_bruteforce(E, k):
+    rng = np.random.default_rng(100 + E)
+    T, d, f = 24, 512, 40
+    x = _rand_bits(rng, (T, d), 1.0)
+    W1, W3, W2 = _rand_bits(rng, (E, f, d), 0.05), _rand_bits(rng, (E, f, d), 0.05), _rand_bits(rng, (E, d, f), 0.05)
+    wr = rng.normal(0, 0.05, size=(d, E)).astype(np.float32)
+    bias = rng.normal(0, 0.5, size=E).astype(np.float32)
+    y, idx, g = ref.layer_tokens(x, wr, bias, W1, W3, W2, k)
+    lg = ref.logits(x, wr, bias)
+    want = _dense_bruteforce(x, lg, W1, W3, W2, k)
+    scale = np.abs(want).max()
+    assert np.max(np.abs(y - want)) <= 1e-7 * scale      # gates are rounded to fp32 (2^-24)
+    assert np.all(np.abs(g.sum(1) - 1) <= 1e-6)          # gates sum to one
+
+
+def test_tiny_config_dense_bruteforce_and_invariants():
+    cfg = synth.PRESETS["tiny"]
+    L = synth.make_layer(cfg)
+    x, wr = synth.bf16_bits(L["x"]), L["w_router"].numpy()
+    W1, W3, W2 = (synth.bf16_bits(L[n]) for n in ("W1", "W3", "W2"))
+    tokens = np.arange(0, cfg.T, 8, dtype=np.int32)
+    y, idx, g = ref.layer_tokens(x, wr, None, W1, W3, W2, cfg.k, tokens)
+    lg = ref.logits(x, wr)
+    want = _dense_bruteforce(x[tokens], lg[tokens], W1, W3, W2, cfg.k)
+    assert np.max(np.abs(y - want)) <= 1e-7 * np.abs(want).max()
+    idx_all, g_all = ref.topk(lg, cfg.k)
+    counts, offsets, perm, inv = ref.permute(idx_all, cfg.E)
+    assert counts.sum() == cfg.T * cfg.k
+    assert np.all(np.abs(g_all.sum(1) - 1) <= 1e-6)
+    assert np.array_equal(idx_all[tokens], idx)
+
+
+def test_linearity_equivariance_zero_row():
+    rng = np.random.default_rng(42)
+    T, d, f, E, k = 12, 512, 32, 4, 2
+    x = _rand_bits(rng, (T, d), 1.0)
+    x[5] = 0                                             # a zero token
+    W1, W3, W2 = _rand_bits(rng, (E, f, d), 0.05), _rand_bits(rng, (E, f, d), 0.05), _rand_bits(rng, (E, d, f), 0.05)
+    wr = rng.normal(0, 0.05, size=(d, E)).astype(np.float32)
+    y, idx, g = ref.layer_tokens(x, wr, None, W1, W3, W2, k)
+    assert np.all(y[5] == 0)
+    # doubling W2 of one expert doubles exactly that expert's contribution
+    e = 1
+    W2b = W2.copy()
+    W2b[e] = _bf16_bits_from_float(2 * (W2[e].astype(np.uint32) << 16).view(np.float32))
+    y2, _, _ = ref.layer_tokens(x, wr, None, W1, W3, W2b, k)
+    xp_rows = np.arange(T)
+    contrib = np.zeros_like(y)
+    for t in xp_rows:
+        for s in range(k):
+            if idx[t, s] == e:
+                o = ref.expert_ffn(x[t:t + 1], np.array([0] * (e + 1) + [1] * (E - e), np.int32), W1, W3, W2)
+                contrib[t] = g[t, s] * o[0]
+    assert np.allclose(y2 - y, contrib, rtol=1e-9, atol=1e-12)
+    assert np.any(contrib != 0)
+    # permuting tokens permutes outputs
+    p = rng.permutation(T)
+    yp, _, _ = ref.layer_tokens(np.ascontiguousarray(x[p]), wr, None, W1, W3, W2, k)
+    assert np.array_equal(yp, y[p])
+
+
+@pytest.mark.parametrize("m", [1, 7, 64, 100, 10 ** 6])
+def test_coalesced_equals_microbatched(m):
+    """Running the stages over micro-batches of any size m reproduces the per-token definition
+    bit for bit (the oracle's statement of Opportunity 1: coalescing changes cost, not results)."""
+    rng = np.random.default_rng(7)
+    T, d, f, E, k = 100, 512, 24, 8, 2
+    x = _rand_bits(rng, (T, d), 1.0)
+    W1, W3, W2 = _rand_bits(rng, (E, f, d), 0.05), _rand_bits(rng, (E, f, d), 0.05), _rand_bits(rng, (E, d, f), 0.05)
+    wr = rng.normal(0, 0.05, size=(d, E)).astype(np.float32)
+    y_def, _, _ = ref.layer_tokens(x, wr, None, W1, W3, W2, k)
+    y_m = ref.layer_staged(x, wr, None, W1, W3, W2, k, m)
+    assert np.array_equal(y_def, y_m)
+
+
+def test_combine_stage_matches_numpy():
+    rng = np.random.default_rng(8)
+    T, d, k = 10, 8, 3
+    yp = rng.normal(size=(T * k, d))
+    inv = rng.permutation(T * k).astype(np.int32)
+    g = rng.random(size=(T, k)).astype(np.float32)
+    want = np.einsum("tk,tkd->td", g.astype(np.float64), yp[inv.reshape(T, k)])
+    assert np.allclose(ref.combine(yp, inv, g), want, rtol=1e-14)
+    bits = _rand_bits(rng, (T * k, d), 1.0)
+    want = np.einsum("tk,tkd->td", g.astype(np.float64), _bf16_to_f64(bits)[inv.reshape(T, k)])
+    assert np.allclose(ref.combine(bits, inv, g), want, rtol=1e-14)
+
+
+def test_argument_errors():
+    with pytest.raises(ValueError):
+        ref.logits(np.zeros((1, 100), np.uint16), np.zeros((100, 2), np.float32))   # d % 512
+    with pytest.raises(ValueError):
+        ref.topk(np.zeros((1, 4), np.float32), 5)                                     # k > E
+    with pytest.raises(ValueError):
+        ref.permute(np.array([[0, 9]], np.int32), 4)                                  # index range
+
+
+# ------------------------------------------------------------------------- cost accounting
+def test_table1_row3_accounting():
+    """Table 1 row 3: per expert D_Y = 6*d_h*d_e bytes, C = 6*rows*d_h*d_e FLOPs."""
+    c = synth.PRESETS["mixtral8x22b_prefill"]
+    assert synth.expert_ffn_flops(c.R, c.d_model, c.d_ff) == 6 * 16384 * 6144 * 16384
+    assert synth.expert_weight_bytes(c.E, c.d_model, c.d_ff) == 8 * 6 * 6144 * 16384
+    assert abs(synth.expert_ffn_flops(c.R, c.d_model, c.d_ff) / 1e12 - 9.896) < 1e-3
+
+
+def test_zipf_calibration_with_oracle_router():
+    cfg = synth.LayerConfig("zipf_small", 4096, 512, 64, 8, 2, seed=77, zipf_s=1.2, empty_expert=True)
+    x = synth.bf16_bits(synth.make_tokens(cfg))
+    wr = synth.make_router(cfg).numpy()
+    base = ref.logits(x, wr)
+
+    def count_fn(bias):
+        idx, _ = ref.topk(base + bias.numpy()[None, :], cfg.k)
+        return np.bincount(idx.reshape(-1), minlength=cfg.E)
+
+    bias = synth.calibrate_expert_bias(cfg, count_fn)
+    counts = count_fn(bias)
+    target = synth.zipf_target_counts(cfg).numpy()
+    live = target > 0
+    assert counts[~live].sum() == 0 and (~live).sum() == 1
+    assert np.all(np.abs(counts[live] - target[live]) <= 0.02 * target[live] + 2)
+    srt = np.sort(target[live])[::-1]
+    assert np.allclose(srt / srt[0], np.arange(1, 8) ** -1.2, rtol=1e-12)
