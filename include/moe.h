@@ -1,0 +1,172 @@
+/*
+ * libmoe — coalesced Mixture-of-Experts layer for AMD MI355X (gfx950), C ABI.
+ *
+ * One MoE layer run over a whole batch of T tokens ("coalesced expert execution": the expert
+ * stage takes the ordinary batch, m_exp = B, instead of a sequence of micro-batches —
+ * paper Section 3.1 Opportunity 1, Section 4.1.1), plus the micro-batched form of the same
+ * call for comparison (paper Section 2.3):
+ *
+ *     y[t] = sum_{s<k} g[t,s] * Expert_{idx[t,s]}(x[t]),
+ *     Expert_e(x) = W2_e ( SiLU(W1_e x) (.) W3_e x ),      SiLU(a) = a / (1 + exp(-a)).
+ *
+ * Conventions for every entry point
+ *   - All tensor pointers are DEVICE pointers on the context's GPU, owned by the caller,
+ *     row-major, densely packed. bf16 tensors are raw 16-bit patterns (moe_bf16).
+ *     The library never frees or keeps a caller pointer after the call returns.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream). Calls enqueue
+ *     work and return without synchronising the host; results are ready when the stream is.
+ *   - Return value: MOE_OK or a negative moe_status. Arguments are checked on the host
+ *     before anything is enqueued; on an argument error nothing has been launched.
+ *   - T = 0 is legal and a no-op. An expert that receives no row is legal.
+ *   - A context is bound to one device and must be used from one stream at a time: its
+ *     workspace is shared by consecutive calls.
+ *   - Supported shapes: d_model a multiple of 512, d_ff a multiple of 256,
+ *     1 <= k <= E <= 64, 0 <= T <= T_max, T_max * k < 2^31 (row offsets into the tensors are
+ *     64-bit inside the kernels). Anything else is MOE_ERR_UNSUPPORTED_SHAPE.
+ *
+ * Weight layout (out, in): W1, W3 are [E, d_ff, d_model]; W2 is [E, d_model, d_ff]; the
+ * router matrix is [d_model, E] fp32. These are the three d_h x d_e bf16 matrices per expert
+ * of the paper's Table 1, row 3.
+ */
+#ifndef MOE_H_
+#define MOE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct moe_ctx moe_ctx;     /* opaque; owns only its own device workspace */
+typedef uint16_t moe_bf16;          /* raw bfloat16 bits */
+
+typedef struct {
+    int32_t T_max;                  /* largest batch (tokens) any call will pass */
+    int32_t d_model;                /* paper's d_h */
+    int32_t d_ff;                   /* paper's d_e */
+    int32_t E;                      /* experts */
+    int32_t k;                      /* experts selected per token */
+} moe_shape;
+
+typedef enum {
+    MOE_OK = 0,
+    MOE_ERR_INVALID_ARG = -1,       /* null pointer, T out of range, bad micro_tokens ... */
+    MOE_ERR_UNSUPPORTED_SHAPE = -2, /* shape outside the supported set listed above */
+    MOE_ERR_WORKSPACE = -3,         /* device allocation failed */
+    MOE_ERR_HIP = -4                /* a HIP runtime call or launch reported an error */
+} moe_status;
+
+/* Stages of the layer, in execution order; indices into moe_profile_end()'s array. */
+enum {
+    MOE_STAGE_ROUTE = 0,            /* router logits + top-k + gates */
+    MOE_STAGE_PERMUTE = 1,          /* histogram, scan, stable scatter */
+    MOE_STAGE_GATHER = 2,           /* x -> x_perm row gather */
+    MOE_STAGE_GATEUP = 3,           /* grouped GEMM  H = SiLU(Xp W1^T) * (Xp W3^T) */
+    MOE_STAGE_DOWN = 4,             /* grouped GEMM  Yp = H W2^T */
+    MOE_STAGE_COMBINE = 5,          /* gate-weighted gather-reduce */
+    MOE_NUM_STAGES = 6
+};
+
+/* Create a context for `shape` on GPU `device_id`; allocates the workspace (routing tables,
+ * x_perm, H and y_perm for T_max tokens). Returns MOE_ERR_UNSUPPORTED_SHAPE for shapes
+ * outside the supported set, MOE_ERR_WORKSPACE if the device allocation fails. */
+int moe_create(moe_ctx** out, const moe_shape* shape, int device_id);
+
+/* Release the context and its workspace. The caller must have drained the stream. */
+int moe_destroy(moe_ctx* ctx);
+
+/* Device bytes moe_create() allocates for `shape` (0 for an unsupported shape). */
+size_t moe_workspace_bytes(const moe_shape* shape);
+
+/* Static, human-readable name of a status code. */
+const char* moe_status_string(int status);
+
+/* Router (paper Section 2.1: each token is routed to the top-k of the experts).
+ *   logits[t,e] = sum_i x[t,i] * w_router[i,e]  (+ bias[e]),  in fp32 with a fixed order:
+ *   64 partial sums, element i = 512*j + 8*l + v goes to partial l and is added by a fused
+ *   multiply-add for j ascending then v ascending; partials combine by the butterfly
+ *   p[l] += p[l xor s], s = 32,16,8,4,2,1; bias is added last.
+ *   topk_idx[t,s] = expert with the (s+1)-th largest logit (ties -> lower index, NaN last);
+ *   topk_w[t,s]   = exp(l_s - l_0) / sum_{s'<k} exp(l_s' - l_0)   (softmax over the selected k).
+ * x [T,d_model] bf16; w_router [d_model,E] fp32; bias [E] fp32 or NULL;
+ * topk_idx [T,k] int32 out; topk_w [T,k] fp32 out; logits_out [T,E] fp32 out or NULL. */
+int moe_route(moe_ctx* ctx, const moe_bf16* x, const float* w_router, const float* bias,
+              int32_t T, int32_t* topk_idx, float* topk_w, float* logits_out, void* stream);
+
+/* The same selection and gates from caller-supplied logits [T,E] fp32. */
+int moe_route_from_logits(moe_ctx* ctx, const float* logits, int32_t T, int32_t* topk_idx,
+                          float* topk_w, void* stream);
+
+/* Group routed rows by expert (the per-expert inputs of paper Section 3.1).
+ * Flat id i = t*k + s. counts[e] = number of ids routed to e; offsets = exclusive prefix sum,
+ * offsets[E] = T*k; rows of one expert keep ascending id (stable), so the result is unique:
+ * perm[p] = i, inv_perm[i] = p. No atomic operation takes part in the ordering.
+ * If x and x_perm are both non-NULL, also gathers x_perm[p,:] = x[perm[p] / k, :].
+ * topk_idx [T,k] int32 (values in [0,E)); counts [E], offsets [E+1], perm [T*k],
+ * inv_perm [T*k] int32 out; x [T,d_model] bf16 or NULL; x_perm [T*k,d_model] bf16 out or NULL.
+ * An index outside [0,E) is not detected on the host; such rows are dropped from every group. */
+int moe_permute(moe_ctx* ctx, const int32_t* topk_idx, int32_t T, int32_t* counts,
+                int32_t* offsets, int32_t* perm, int32_t* inv_perm, const moe_bf16* x,
+                moe_bf16* x_perm, void* stream);
+
+/* Grouped SwiGLU expert FFN over rows already grouped by expert (paper Table 1 row 3,
+ * "gated FFN execution per expert"): for offsets[e] <= p < offsets[e+1],
+ *   y_perm[p,:] = W2_e ( SiLU(W1_e x_perm[p,:]) (.) W3_e x_perm[p,:] ).
+ * bf16 operands, fp32 accumulation on the matrix cores, the intermediate H and y_perm
+ * rounded to bf16 (nearest even). R = number of rows = offsets[E] (R <= T_max*k).
+ * x_perm [R,d_model]; offsets [E+1] int32 (device); W1, W3 [E,d_ff,d_model]; W2 [E,d_model,d_ff];
+ * y_perm [R,d_model] bf16 out. Per-element accumulation order does not depend on R. */
+int moe_expert_ffn(moe_ctx* ctx, const moe_bf16* x_perm, const int32_t* offsets, int32_t R,
+                   const moe_bf16* W1, const moe_bf16* W3, const moe_bf16* W2, moe_bf16* y_perm,
+                   void* stream);
+
+/* Gate-weighted combine:  y[t,:] = sum_{s<k} topk_w[t,s] * y_perm[inv_perm[t*k+s], :],
+ * slots added in order s = 0..k-1 in fp32, rounded once to bf16. A gather: deterministic.
+ * y_perm [T*k,d_model] bf16; inv_perm [T*k] int32; topk_w [T,k] fp32; y [T,d_model] bf16 out. */
+int moe_combine(moe_ctx* ctx, const moe_bf16* y_perm, const int32_t* inv_perm,
+                const float* topk_w, int32_t T, moe_bf16* y, void* stream);
+
+/* The whole layer over the coalesced batch (paper Section 4.1.1: m_exp = B):
+ * route -> permute(+gather) -> expert FFN -> combine, intermediates in the context workspace.
+ * x [T,d_model]; w_router [d_model,E]; bias [E] or NULL; W1, W3, W2 as above; y [T,d_model] out. */
+int moe_layer_forward(moe_ctx* ctx, const moe_bf16* x, const float* w_router, const float* bias,
+                      const moe_bf16* W1, const moe_bf16* W3, const moe_bf16* W2, int32_t T,
+                      moe_bf16* y, void* stream);
+
+/* The same layer as consecutive micro-batches of `micro_tokens` tokens (the last may be
+ * shorter), run one after the other on `stream` through the same expert weights, each with
+ * its own routing and permutation (paper Section 2.3, Section 3.1). The output equals
+ * moe_layer_forward's bit for bit; only the cost differs. micro_tokens >= 1. */
+int moe_layer_forward_microbatched(moe_ctx* ctx, const moe_bf16* x, const float* w_router,
+                                   const float* bias, const moe_bf16* W1, const moe_bf16* W3,
+                                   const moe_bf16* W2, int32_t T, int32_t micro_tokens,
+                                   moe_bf16* y, void* stream);
+
+/* Copy the routing tables that the last moe_layer_forward call on this context left in the
+ * workspace into caller tensors (device-to-device copies enqueued on `stream`); for the
+ * micro-batched call they are the tables of its last micro-batch. T is that call's token count.
+ * topk_idx [T,k] int32, topk_w [T,k] fp32, counts [E], offsets [E+1], perm [T*k],
+ * inv_perm [T*k] int32; any destination may be NULL. */
+int moe_last_routing(moe_ctx* ctx, int32_t T, int32_t* topk_idx, float* topk_w, int32_t* counts,
+                     int32_t* offsets, int32_t* perm, int32_t* inv_perm, void* stream);
+
+/* Per-stage device timing for measurement. moe_profile_begin() arms up to `max_calls`
+ * subsequent moe_layer_forward / moe_layer_forward_microbatched calls: each records HIP
+ * events on the caller's stream between stages. moe_profile_end() waits for those events and
+ * writes, per stage, the total milliseconds (stage_ms[MOE_NUM_STAGES], host), the number of
+ * kernel launches (stage_launches[MOE_NUM_STAGES], host) and the number of layer calls
+ * covered (*calls), then disarms. Costs two event records per stage while armed. */
+int moe_profile_begin(moe_ctx* ctx, int32_t max_calls);
+int moe_profile_end(moe_ctx* ctx, double* stage_ms, int64_t* stage_launches, int32_t* calls);
+
+/* Tuning / testing knob, process-wide: force the expert-GEMM tile configuration
+ * (0 = large, 1 = medium, 2 = small rows-per-expert tile) or -1 for the automatic choice by
+ * average rows per expert. Every configuration produces identical bits (same accumulation
+ * chain per output element); only speed differs. Returns MOE_ERR_INVALID_ARG otherwise. */
+int moe_set_gemm_config(int config);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE_H_ */

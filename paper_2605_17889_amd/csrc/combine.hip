@@ -1,0 +1,61 @@
+// Gate-weighted combine of expert outputs:  y[t,:] = sum_{s<k} g[t,s] * y_perm[inv_perm[t*k+s],:]
+// (the layer's defining sum over the selected experts). A per-token gather with a fixed slot
+// order in fp32, so the result is deterministic; no scatter, no atomics.
+//
+// HBM traffic per token: 2*d_model*k bytes read, 2*d_model bytes written.
+#include "common.h"
+
+namespace moe {
+namespace {
+
+constexpr int kMaxSlots = 64;
+
+// One block per token; each thread owns 8 consecutive columns (one 16-byte vector) per step.
+__global__ __launch_bounds__(256) void combine_kernel(const uint16_t* __restrict__ y_perm,
+                                                      const int32_t* __restrict__ inv_perm,
+                                                      const float* __restrict__ topk_w, int R,
+                                                      int d, int k, uint16_t* __restrict__ y) {
+    const int t = blockIdx.x;
+    __shared__ int32_t row[kMaxSlots];
+    __shared__ float gate[kMaxSlots];
+    if (threadIdx.x < k) {
+        row[threadIdx.x] = inv_perm[static_cast<size_t>(t) * k + threadIdx.x];
+        gate[threadIdx.x] = topk_w[static_cast<size_t>(t) * k + threadIdx.x];
+    }
+    __syncthreads();
+    for (int c = threadIdx.x; c < d / 8; c += blockDim.x) {
+        float acc[8];
+#pragma unroll
+        for (int v = 0; v < 8; ++v) acc[v] = 0.f;
+        for (int s = 0; s < k; ++s) {
+            const int p = row[s];
+            if (static_cast<unsigned>(p) >= static_cast<unsigned>(R)) continue;  // dropped row
+            const float g = gate[s];
+            const uint4 q = reinterpret_cast<const uint4*>(y_perm + static_cast<size_t>(p) * d)[c];
+            const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                acc[2 * v] = fmaf(g, __uint_as_float(w[v] << 16), acc[2 * v]);
+                acc[2 * v + 1] = fmaf(g, __uint_as_float(w[v] & 0xffff0000u), acc[2 * v + 1]);
+            }
+        }
+        uint4 o;
+        o.x = f32_to_bf16(acc[0]) | (static_cast<uint32_t>(f32_to_bf16(acc[1])) << 16);
+        o.y = f32_to_bf16(acc[2]) | (static_cast<uint32_t>(f32_to_bf16(acc[3])) << 16);
+        o.z = f32_to_bf16(acc[4]) | (static_cast<uint32_t>(f32_to_bf16(acc[5])) << 16);
+        o.w = f32_to_bf16(acc[6]) | (static_cast<uint32_t>(f32_to_bf16(acc[7])) << 16);
+        reinterpret_cast<uint4*>(y + static_cast<size_t>(t) * d)[c] = o;
+    }
+}
+
+}  // namespace
+
+int launch_combine(const moe_bf16* y_perm, const int32_t* inv_perm, const float* topk_w, int T,
+                   int d, int k, moe_bf16* y, hipStream_t s) {
+    if (T == 0) return MOE_OK;
+    hipLaunchKernelGGL(combine_kernel, dim3(T), dim3(256), 0, s, y_perm, inv_perm, topk_w, T * k, d,
+                       k, y);
+    return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
+}
+
+}  // namespace moe

@@ -1,0 +1,48 @@
+// Internal helpers shared by the HIP translation units of libmoe (not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "moe.h"
+
+namespace moe {
+
+constexpr int kWave = 64;        // CDNA wavefront width
+constexpr int kMaxExperts = 64;  // one lane per expert in the permutation kernels
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) {
+    return __uint_as_float(static_cast<uint32_t>(b) << 16);
+}
+
+// fp32 -> bf16, round to nearest even; NaN stays a quiet NaN.
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return static_cast<uint16_t>((u >> 16) | 0x0040u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return static_cast<uint16_t>(u >> 16);
+}
+
+#define MOE_HIP_TRY(expr)                         \
+    do {                                          \
+        hipError_t e__ = (expr);                  \
+        if (e__ != hipSuccess) return MOE_ERR_HIP; \
+    } while (0)
+
+// Launch wrappers (defined in the .hip files). Each returns a moe_status and only enqueues.
+int launch_route(const moe_bf16* x, const float* w_router, const float* bias, int T, int d, int E,
+                 int k, int32_t* topk_idx, float* topk_w, float* logits_out, hipStream_t s);
+int launch_route_from_logits(const float* logits, int T, int E, int k, int32_t* topk_idx,
+                             float* topk_w, hipStream_t s);
+size_t permute_scratch_ints(int R_max, int E);
+int launch_permute(const int32_t* topk_idx, int R, int E, int32_t* counts, int32_t* offsets,
+                   int32_t* perm, int32_t* inv_perm, int32_t* scratch, hipStream_t s);
+int launch_gather(const moe_bf16* x, const int32_t* perm, const int32_t* offsets, int R, int d,
+                  int k, int E, moe_bf16* x_perm, hipStream_t s);
+int launch_gateup(const moe_bf16* x_perm, const int32_t* offsets, int R, int d, int f, int E,
+                  const moe_bf16* W1, const moe_bf16* W3, moe_bf16* H, hipStream_t s);
+int launch_down(const moe_bf16* H, const int32_t* offsets, int R, int d, int f, int E,
+                const moe_bf16* W2, moe_bf16* y_perm, hipStream_t s);
+int launch_combine(const moe_bf16* y_perm, const int32_t* inv_perm, const float* topk_w, int T,
+                   int d, int k, moe_bf16* y, hipStream_t s);
+
+}  // namespace moe

@@ -1,0 +1,339 @@
+// C-ABI entry points of libmoe: argument validation, workspace, stage sequencing and the
+// optional per-stage event timing. All arithmetic lives in the kernels of the other files.
+#include <new>
+#include <vector>
+
+#include "common.h"
+
+namespace moe {
+void set_gemm_config(int cfg);
+}
+
+struct moe_ctx {
+    moe_shape shape;
+    int device;
+    // workspace (device)
+    unsigned char* base;
+    size_t bytes;
+    int32_t* topk_idx;   // [T_max, k]
+    float* topk_w;       // [T_max, k]
+    int32_t* counts;     // [E]
+    int32_t* offsets;    // [E+1]
+    int32_t* perm;       // [R_max]
+    int32_t* inv_perm;   // [R_max]
+    int32_t* scratch;    // permutation segment tables
+    moe_bf16* x_perm;    // [R_max, d]
+    moe_bf16* H;         // [R_max, f]
+    moe_bf16* y_perm;    // [R_max, d]
+    // profiling
+    bool prof_armed;
+    int prof_max_calls, prof_calls;
+    std::vector<hipEvent_t> prof_events;       // per recorded interval: start, stop
+    std::vector<int> prof_stage;               // stage of each interval
+    int64_t prof_launches[MOE_NUM_STAGES];
+};
+
+namespace {
+
+using namespace moe;
+
+bool shape_ok(const moe_shape* s) {
+    if (!s) return false;
+    if (s->T_max < 0 || s->d_model <= 0 || s->d_ff <= 0 || s->E <= 0 || s->k <= 0) return false;
+    if (s->d_model % 512 != 0 || s->d_ff % 256 != 0) return false;
+    if (s->E > kMaxExperts || s->k > s->E) return false;
+    if (static_cast<long long>(s->T_max) * s->k >= (1LL << 31)) return false;
+    return true;
+}
+
+size_t align_up(size_t v) { return (v + 255) & ~static_cast<size_t>(255); }
+
+struct Layout {
+    size_t topk_idx, topk_w, counts, offsets, perm, inv_perm, scratch, x_perm, H, y_perm, total;
+};
+
+Layout layout_for(const moe_shape* s) {
+    Layout L{};
+    const size_t T = static_cast<size_t>(s->T_max), R = T * s->k;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t at = off; off = align_up(off + bytes); return at; };
+    L.topk_idx = take(R * 4);
+    L.topk_w = take(R * 4);
+    L.counts = take(static_cast<size_t>(s->E) * 4);
+    L.offsets = take(static_cast<size_t>(s->E + 1) * 4);
+    L.perm = take(R * 4);
+    L.inv_perm = take(R * 4);
+    L.scratch = take(permute_scratch_ints(static_cast<int>(R), s->E) * 4);
+    L.x_perm = take(R * s->d_model * 2);
+    L.H = take(R * s->d_ff * 2);
+    L.y_perm = take(R * s->d_model * 2);
+    L.total = off ? off : 256;
+    return L;
+}
+
+// Stage timing: records a start/stop event pair around `fn` when armed.
+template <typename Fn>
+int run_stage(moe_ctx* c, int stage, int launches, hipStream_t s, Fn&& fn) {
+    const bool rec = c->prof_armed && c->prof_calls <= c->prof_max_calls;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (rec) {
+        MOE_HIP_TRY(hipEventCreate(&e0));
+        MOE_HIP_TRY(hipEventCreate(&e1));
+        MOE_HIP_TRY(hipEventRecord(e0, s));
+    }
+    const int rc = fn();
+    if (rec) {
+        MOE_HIP_TRY(hipEventRecord(e1, s));
+        c->prof_events.push_back(e0);
+        c->prof_events.push_back(e1);
+        c->prof_stage.push_back(stage);
+        c->prof_launches[stage] += launches;
+    }
+    return rc;
+}
+
+int forward_chunk(moe_ctx* c, const moe_bf16* x, const float* w_router, const float* bias,
+                  const moe_bf16* W1, const moe_bf16* W3, const moe_bf16* W2, int T, moe_bf16* y,
+                  hipStream_t s) {
+    const moe_shape& sh = c->shape;
+    const int d = sh.d_model, f = sh.d_ff, E = sh.E, k = sh.k, R = T * k;
+    int rc;
+    rc = run_stage(c, MOE_STAGE_ROUTE, 1, s, [&] {
+        return launch_route(x, w_router, bias, T, d, E, k, c->topk_idx, c->topk_w, nullptr, s);
+    });
+    if (rc != MOE_OK) return rc;
+    rc = run_stage(c, MOE_STAGE_PERMUTE, 3, s, [&] {
+        return launch_permute(c->topk_idx, R, E, c->counts, c->offsets, c->perm, c->inv_perm,
+                              c->scratch, s);
+    });
+    if (rc != MOE_OK) return rc;
+    rc = run_stage(c, MOE_STAGE_GATHER, 1, s,
+                   [&] { return launch_gather(x, c->perm, c->offsets, R, d, k, E, c->x_perm, s); });
+    if (rc != MOE_OK) return rc;
+    rc = run_stage(c, MOE_STAGE_GATEUP, 1, s, [&] {
+        return launch_gateup(c->x_perm, c->offsets, R, d, f, E, W1, W3, c->H, s);
+    });
+    if (rc != MOE_OK) return rc;
+    rc = run_stage(c, MOE_STAGE_DOWN, 1, s, [&] {
+        return launch_down(c->H, c->offsets, R, d, f, E, W2, c->y_perm, s);
+    });
+    if (rc != MOE_OK) return rc;
+    return run_stage(c, MOE_STAGE_COMBINE, 1, s, [&] {
+        return launch_combine(c->y_perm, c->inv_perm, c->topk_w, T, d, k, y, s);
+    });
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* moe_status_string(int status) {
+    switch (status) {
+        case MOE_OK: return "MOE_OK";
+        case MOE_ERR_INVALID_ARG: return "MOE_ERR_INVALID_ARG";
+        case MOE_ERR_UNSUPPORTED_SHAPE: return "MOE_ERR_UNSUPPORTED_SHAPE";
+        case MOE_ERR_WORKSPACE: return "MOE_ERR_WORKSPACE";
+        case MOE_ERR_HIP: return "MOE_ERR_HIP";
+        default: return "MOE_ERR_UNKNOWN";
+    }
+}
+
+size_t moe_workspace_bytes(const moe_shape* shape) {
+    if (!shape_ok(shape)) return 0;
+    return layout_for(shape).total;
+}
+
+int moe_create(moe_ctx** out, const moe_shape* shape, int device_id) {
+    if (!out) return MOE_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (!shape) return MOE_ERR_INVALID_ARG;
+    if (!shape_ok(shape)) return MOE_ERR_UNSUPPORTED_SHAPE;
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess) return MOE_ERR_HIP;
+    if (device_id < 0 || device_id >= ndev) return MOE_ERR_INVALID_ARG;
+    MOE_HIP_TRY(hipSetDevice(device_id));
+    moe_ctx* c = new (std::nothrow) moe_ctx();
+    if (!c) return MOE_ERR_WORKSPACE;
+    c->shape = *shape;
+    c->device = device_id;
+    const Layout L = layout_for(shape);
+    c->bytes = L.total;
+    void* p = nullptr;
+    if (hipMalloc(&p, L.total) != hipSuccess) {
+        (void)hipGetLastError();
+        delete c;
+        return MOE_ERR_WORKSPACE;
+    }
+    c->base = static_cast<unsigned char*>(p);
+    c->topk_idx = reinterpret_cast<int32_t*>(c->base + L.topk_idx);
+    c->topk_w = reinterpret_cast<float*>(c->base + L.topk_w);
+    c->counts = reinterpret_cast<int32_t*>(c->base + L.counts);
+    c->offsets = reinterpret_cast<int32_t*>(c->base + L.offsets);
+    c->perm = reinterpret_cast<int32_t*>(c->base + L.perm);
+    c->inv_perm = reinterpret_cast<int32_t*>(c->base + L.inv_perm);
+    c->scratch = reinterpret_cast<int32_t*>(c->base + L.scratch);
+    c->x_perm = reinterpret_cast<moe_bf16*>(c->base + L.x_perm);
+    c->H = reinterpret_cast<moe_bf16*>(c->base + L.H);
+    c->y_perm = reinterpret_cast<moe_bf16*>(c->base + L.y_perm);
+    c->prof_armed = false;
+    c->prof_max_calls = c->prof_calls = 0;
+    for (auto& v : c->prof_launches) v = 0;
+    *out = c;
+    return MOE_OK;
+}
+
+int moe_destroy(moe_ctx* c) {
+    if (!c) return MOE_ERR_INVALID_ARG;
+    for (hipEvent_t e : c->prof_events) (void)hipEventDestroy(e);
+    int rc = MOE_OK;
+    if (c->base && hipFree(c->base) != hipSuccess) rc = MOE_ERR_HIP;
+    delete c;
+    return rc;
+}
+
+int moe_route(moe_ctx* c, const moe_bf16* x, const float* w_router, const float* bias, int32_t T,
+              int32_t* topk_idx, float* topk_w, float* logits_out, void* stream) {
+    if (!c || T < 0 || T > c->shape.T_max) return MOE_ERR_INVALID_ARG;
+    if (T == 0) return MOE_OK;
+    if (!x || !w_router || !topk_idx || !topk_w) return MOE_ERR_INVALID_ARG;
+    return launch_route(x, w_router, bias, T, c->shape.d_model, c->shape.E, c->shape.k, topk_idx,
+                        topk_w, logits_out, static_cast<hipStream_t>(stream));
+}
+
+int moe_route_from_logits(moe_ctx* c, const float* logits, int32_t T, int32_t* topk_idx,
+                          float* topk_w, void* stream) {
+    if (!c || T < 0 || T > c->shape.T_max) return MOE_ERR_INVALID_ARG;
+    if (T == 0) return MOE_OK;
+    if (!logits || !topk_idx || !topk_w) return MOE_ERR_INVALID_ARG;
+    return launch_route_from_logits(logits, T, c->shape.E, c->shape.k, topk_idx, topk_w,
+                                    static_cast<hipStream_t>(stream));
+}
+
+int moe_permute(moe_ctx* c, const int32_t* topk_idx, int32_t T, int32_t* counts, int32_t* offsets,
+                int32_t* perm, int32_t* inv_perm, const moe_bf16* x, moe_bf16* x_perm,
+                void* stream) {
+    if (!c || T < 0 || T > c->shape.T_max) return MOE_ERR_INVALID_ARG;
+    if (!counts || !offsets) return MOE_ERR_INVALID_ARG;
+    if (T > 0 && (!topk_idx || !perm || !inv_perm)) return MOE_ERR_INVALID_ARG;
+    if ((x == nullptr) != (x_perm == nullptr)) return MOE_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int R = T * c->shape.k;
+    int rc = launch_permute(topk_idx, R, c->shape.E, counts, offsets, perm, inv_perm, c->scratch, s);
+    if (rc != MOE_OK) return rc;
+    if (x && T > 0)
+        rc = launch_gather(x, perm, offsets, R, c->shape.d_model, c->shape.k, c->shape.E, x_perm, s);
+    return rc;
+}
+
+int moe_expert_ffn(moe_ctx* c, const moe_bf16* x_perm, const int32_t* offsets, int32_t R,
+                   const moe_bf16* W1, const moe_bf16* W3, const moe_bf16* W2, moe_bf16* y_perm,
+                   void* stream) {
+    if (!c || R < 0 || static_cast<long long>(R) > static_cast<long long>(c->shape.T_max) * c->shape.k)
+        return MOE_ERR_INVALID_ARG;
+    if (R == 0) return MOE_OK;
+    if (!x_perm || !offsets || !W1 || !W3 || !W2 || !y_perm) return MOE_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const moe_shape& sh = c->shape;
+    int rc = launch_gateup(x_perm, offsets, R, sh.d_model, sh.d_ff, sh.E, W1, W3, c->H, s);
+    if (rc != MOE_OK) return rc;
+    return launch_down(c->H, offsets, R, sh.d_model, sh.d_ff, sh.E, W2, y_perm, s);
+}
+
+int moe_combine(moe_ctx* c, const moe_bf16* y_perm, const int32_t* inv_perm, const float* topk_w,
+                int32_t T, moe_bf16* y, void* stream) {
+    if (!c || T < 0 || T > c->shape.T_max) return MOE_ERR_INVALID_ARG;
+    if (T == 0) return MOE_OK;
+    if (!y_perm || !inv_perm || !topk_w || !y) return MOE_ERR_INVALID_ARG;
+    return launch_combine(y_perm, inv_perm, topk_w, T, c->shape.d_model, c->shape.k, y,
+                          static_cast<hipStream_t>(stream));
+}
+
+int moe_layer_forward(moe_ctx* c, const moe_bf16* x, const float* w_router, const float* bias,
+                      const moe_bf16* W1, const moe_bf16* W3, const moe_bf16* W2, int32_t T,
+                      moe_bf16* y, void* stream) {
+    if (!c || T < 0 || T > c->shape.T_max) return MOE_ERR_INVALID_ARG;
+    if (T == 0) return MOE_OK;
+    if (!x || !w_router || !W1 || !W3 || !W2 || !y) return MOE_ERR_INVALID_ARG;
+    if (c->prof_armed) c->prof_calls++;
+    return forward_chunk(c, x, w_router, bias, W1, W3, W2, T, y, static_cast<hipStream_t>(stream));
+}
+
+int moe_layer_forward_microbatched(moe_ctx* c, const moe_bf16* x, const float* w_router,
+                                   const float* bias, const moe_bf16* W1, const moe_bf16* W3,
+                                   const moe_bf16* W2, int32_t T, int32_t micro_tokens,
+                                   moe_bf16* y, void* stream) {
+    if (!c || T < 0 || T > c->shape.T_max || micro_tokens < 1) return MOE_ERR_INVALID_ARG;
+    if (T == 0) return MOE_OK;
+    if (!x || !w_router || !W1 || !W3 || !W2 || !y) return MOE_ERR_INVALID_ARG;
+    if (c->prof_armed) c->prof_calls++;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const size_t d = static_cast<size_t>(c->shape.d_model);
+    for (int t0 = 0; t0 < T; t0 += micro_tokens) {
+        const int Tc = (T - t0 < micro_tokens) ? T - t0 : micro_tokens;
+        const int rc = forward_chunk(c, x + t0 * d, w_router, bias, W1, W3, W2, Tc, y + t0 * d, s);
+        if (rc != MOE_OK) return rc;
+    }
+    return MOE_OK;
+}
+
+int moe_last_routing(moe_ctx* c, int32_t T, int32_t* topk_idx, float* topk_w, int32_t* counts,
+                     int32_t* offsets, int32_t* perm, int32_t* inv_perm, void* stream) {
+    if (!c || T < 0 || T > c->shape.T_max) return MOE_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const size_t R = static_cast<size_t>(T) * c->shape.k, E = static_cast<size_t>(c->shape.E);
+    auto copy = [&](void* dst, const void* src, size_t bytes) -> int {
+        if (!dst || bytes == 0) return MOE_OK;
+        return hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToDevice, s) == hipSuccess ? MOE_OK
+                                                                                        : MOE_ERR_HIP;
+    };
+    int rc = copy(topk_idx, c->topk_idx, R * 4);
+    if (rc == MOE_OK) rc = copy(topk_w, c->topk_w, R * 4);
+    if (rc == MOE_OK) rc = copy(counts, c->counts, E * 4);
+    if (rc == MOE_OK) rc = copy(offsets, c->offsets, (E + 1) * 4);
+    if (rc == MOE_OK) rc = copy(perm, c->perm, R * 4);
+    if (rc == MOE_OK) rc = copy(inv_perm, c->inv_perm, R * 4);
+    return rc;
+}
+
+int moe_profile_begin(moe_ctx* c, int32_t max_calls) {
+    if (!c || max_calls < 1) return MOE_ERR_INVALID_ARG;
+    for (hipEvent_t e : c->prof_events) (void)hipEventDestroy(e);
+    c->prof_events.clear();
+    c->prof_stage.clear();
+    for (auto& v : c->prof_launches) v = 0;
+    c->prof_armed = true;
+    c->prof_max_calls = max_calls;
+    c->prof_calls = 0;
+    return MOE_OK;
+}
+
+int moe_profile_end(moe_ctx* c, double* stage_ms, int64_t* stage_launches, int32_t* calls) {
+    if (!c || !stage_ms || !stage_launches || !calls) return MOE_ERR_INVALID_ARG;
+    if (!c->prof_armed) return MOE_ERR_INVALID_ARG;
+    c->prof_armed = false;
+    for (int i = 0; i < MOE_NUM_STAGES; ++i) { stage_ms[i] = 0.0; stage_launches[i] = c->prof_launches[i]; }
+    int rc = MOE_OK;
+    for (size_t i = 0; i < c->prof_stage.size(); ++i) {
+        hipEvent_t e0 = c->prof_events[2 * i], e1 = c->prof_events[2 * i + 1];
+        float ms = 0.f;
+        if (hipEventSynchronize(e1) != hipSuccess || hipEventElapsedTime(&ms, e0, e1) != hipSuccess)
+            rc = MOE_ERR_HIP;
+        else
+            stage_ms[c->prof_stage[i]] += ms;
+    }
+    *calls = c->prof_calls < c->prof_max_calls ? c->prof_calls : c->prof_max_calls;
+    for (hipEvent_t e : c->prof_events) (void)hipEventDestroy(e);
+    c->prof_events.clear();
+    c->prof_stage.clear();
+    return rc;
+}
+
+/* Tuning/testing knob: force the expert-GEMM tile configuration (0 large, 1 medium, 2 small
+ * rows-per-expert), or -1 for the automatic choice. All configurations give identical bits. */
+int moe_set_gemm_config(int config) {
+    if (config < -1 || config > 2) return MOE_ERR_INVALID_ARG;
+    moe::set_gemm_config(config);
+    return MOE_OK;
+}
+
+}  // extern "C"

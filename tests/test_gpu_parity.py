@@ -1,0 +1,451 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle on the same seeded
+inputs. Integer outputs must match bit for bit; floating-point outputs within
+rel-L2 <= 1e-2 and max-abs <= 2e-2 * max|y_ref| (bf16 operands, fp32 accumulation)."""
+import json
+import os
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import ref
+from paper_2605_17889_amd import binding as B
+from paper_2605_17889_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+REL_L2_TOL = 1e-2
+MAX_ABS_TOL = 2e-2
+GATE_TOL = 1e-6
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def dev(a, dtype=None):
+    t = torch.as_tensor(a)
+    if dtype is not None:
+        t = t.to(dtype)
+    return t.cuda().contiguous()
+
+
+def bits(t):
+    return synth.bf16_bits(t)
+
+
+def bf16_to_f64(bits_):
+    return (bits_.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
+def bf16_tensor_from_bits(b):
+    return torch.from_numpy(b.view(np.int16)).view(torch.bfloat16)
+
+
+def assert_close_ffn(got_bf16_bits, want_f64, what):
+    got = bf16_to_f64(got_bf16_bits)
+    scale = np.abs(want_f64).max()
+    if scale == 0:
+        assert np.all(got == 0), what
+        return 0.0, 0.0
+    rel = np.linalg.norm(got - want_f64) / np.linalg.norm(want_f64)
+    mx = np.abs(got - want_f64).max() / scale
+    say(f"    {what}: rel-L2 {rel:.3e}  max-abs/max|ref| {mx:.3e}")
+    assert rel <= REL_L2_TOL, (what, rel)
+    assert mx <= MAX_ABS_TOL, (what, mx)
+    return rel, mx
+
+
+def rand_bits(rng, shape, std):
+    return bits(torch.tensor(rng.normal(0, std, size=shape), dtype=torch.float32).bfloat16())
+
+
+# ------------------------------------------------------------------------------- routing
+@pytest.mark.parametrize("T,d,E,k,use_bias", [
+    (1, 512, 8, 2, False), (3, 512, 8, 2, True), (257, 1024, 8, 2, False), (130, 512, 5, 3, True),
+    (64, 512, 16, 4, False), (33, 512, 33, 6, True), (70, 512, 64, 8, True), (19, 1536, 8, 8, False),
+    (5, 512, 1, 1, False),
+])
+def test_route_bit_exact(T, d, E, k, use_bias):
+    say(f"route T={T} d={d} E={E} k={k} bias={use_bias}")
+    rng = np.random.default_rng(T * 1000 + E)
+    x = rand_bits(rng, (T, d), 1.0)
+    wr = rng.normal(0, 0.02, size=(d, E)).astype(np.float32)
+    bias = rng.normal(0, 0.3, size=E).astype(np.float32) if use_bias else None
+    lg_ref = ref.logits(x, wr, bias)
+    idx_ref, g_ref = ref.topk(lg_ref, k)
+
+    ctx = B.MoeContext(max(T, 1), d, 256, E, k)
+    idx = torch.empty((T, k), dtype=torch.int32, device="cuda")
+    g = torch.empty((T, k), dtype=torch.float32, device="cuda")
+    lg = torch.empty((T, E), dtype=torch.float32, device="cuda")
+    B.moe_route(ctx, dev(bf16_tensor_from_bits(x)), dev(wr), None if bias is None else dev(bias), T,
+                idx, g, lg)
+    torch.cuda.synchronize()
+    assert np.array_equal(lg.cpu().numpy().view(np.uint32), lg_ref.view(np.uint32))   # logits bit-exact
+    assert np.array_equal(idx.cpu().numpy(), idx_ref)
+    assert np.max(np.abs(g.cpu().numpy() - g_ref)) <= GATE_TOL
+    assert np.max(np.abs(g.cpu().numpy().sum(1) - 1)) <= GATE_TOL
+    # the same selection from supplied logits
+    idx2 = torch.empty_like(idx)
+    g2 = torch.empty_like(g)
+    B.moe_route_from_logits(ctx, lg, T, idx2, g2)
+    torch.cuda.synchronize()
+    assert torch.equal(idx2, idx) and torch.equal(g2, g)
+    ctx.close()
+
+
+def test_route_golden_tree_cases_on_gpu():
+    cases = json.load(open(os.path.join(GOLD, "route_tree_cases.json")))["cases"]
+    hx = lambda s: float.fromhex(s)
+    for case in cases:
+        say(f"route golden {case['name']}")
+        d, E = case["d"], case["E"]
+        x = np.zeros((1, d), np.float32)
+        for i, v in case["x"].items():
+            x[0, int(i)] = hx(v)
+        w = np.full((d, E), hx(case["w_default"]), np.float32)
+        for key, v in case["w"].items():
+            i, e = (int(s) for s in key.split(",")) if "," in key else (int(key), 0)
+            w[i, e] = hx(v)
+        bias = None if case["bias"] is None else np.array([hx(b) for b in case["bias"]], np.float32)
+        ctx = B.MoeContext(1, d, 256, E, 1)
+        idx = torch.empty((1, 1), dtype=torch.int32, device="cuda")
+        g = torch.empty((1, 1), dtype=torch.float32, device="cuda")
+        lg = torch.empty((1, E), dtype=torch.float32, device="cuda")
+        B.moe_route(ctx, dev(x, torch.bfloat16), dev(w), None if bias is None else dev(bias), 1, idx, g, lg)
+        torch.cuda.synchronize()
+        want = np.array([hx(v) for v in case["expected"]], np.float32)
+        assert np.array_equal(lg.cpu().numpy()[0].view(np.uint32), want.view(np.uint32)), case["name"]
+        ctx.close()
+
+
+def test_route_from_logits_golden_ties():
+    cases = json.load(open(os.path.join(GOLD, "topk_cases.json")))["cases"]
+    for case in cases:
+        lg = np.array([[float(v) for v in case["logits"]]], np.float32)
+        E, k = lg.shape[1], case["k"]
+        ctx = B.MoeContext(1, 512, 256, E, k)
+        idx = torch.empty((1, k), dtype=torch.int32, device="cuda")
+        g = torch.empty((1, k), dtype=torch.float32, device="cuda")
+        B.moe_route_from_logits(ctx, dev(lg), 1, idx, g)
+        torch.cuda.synchronize()
+        assert idx.cpu().numpy()[0].tolist() == case["idx"], case["name"]
+        if "gates" in case:
+            assert np.allclose(g.cpu().numpy()[0], case["gates"], atol=GATE_TOL)
+        ctx.close()
+
+
+# --------------------------------------------------------------------------- permutation
+@pytest.mark.parametrize("T,E,k,seed,empty", [
+    (1, 8, 2, 0, False), (37, 8, 2, 1, True), (256, 8, 2, 2, False), (1000, 64, 6, 3, False),
+    (4096, 8, 2, 4, True), (777, 3, 3, 5, False), (16384, 8, 2, 6, False), (129, 40, 1, 7, True),
+])
+def test_permute_bit_exact(T, E, k, seed, empty):
+    say(f"permute T={T} E={E} k={k} empty={empty}")
+    rng = np.random.default_rng(seed)
+    pool = np.arange(E) if not (empty and E > k) else np.delete(np.arange(E), E // 2)
+    idx = np.stack([rng.permutation(pool)[:k] for _ in range(T)]).astype(np.int32)
+    d = 512
+    x = rand_bits(rng, (T, d), 1.0)
+    c_ref, o_ref, p_ref, i_ref = ref.permute(idx, E)
+    xp_ref = ref.gather(x, p_ref, k)
+
+    ctx = B.MoeContext(T, d, 256, E, k)
+    R = T * k
+    counts = torch.empty(E, dtype=torch.int32, device="cuda")
+    offsets = torch.empty(E + 1, dtype=torch.int32, device="cuda")
+    perm = torch.empty(R, dtype=torch.int32, device="cuda")
+    inv = torch.empty(R, dtype=torch.int32, device="cuda")
+    xp = torch.empty((R, d), dtype=torch.bfloat16, device="cuda")
+    B.moe_permute(ctx, dev(idx), T, counts, offsets, perm, inv, dev(bf16_tensor_from_bits(x)), xp)
+    torch.cuda.synchronize()
+    assert np.array_equal(counts.cpu().numpy(), c_ref)
+    assert np.array_equal(offsets.cpu().numpy(), o_ref)
+    assert np.array_equal(perm.cpu().numpy(), p_ref)
+    assert np.array_equal(inv.cpu().numpy(), i_ref)
+    assert np.array_equal(bits(xp), xp_ref)
+    assert int(counts.sum()) == R
+    ctx.close()
+
+
+# ---------------------------------------------------------------- expert FFN and combine
+@pytest.mark.parametrize("config", [0, 1, 2])
+@pytest.mark.parametrize("d,f,rows", [
+    (512, 256, [300, 0, 1, 77]),          # empty expert, single row, ragged tails
+    (512, 512, [256, 257, 64, 31, 0, 5, 128, 129]),
+    (1024, 768, [513, 40]),
+])
+def test_expert_ffn_parity(config, d, f, rows):
+    say(f"expert_ffn config={config} d={d} f={f} rows={rows}")
+    rng = np.random.default_rng(d + f + len(rows))
+    E = len(rows)
+    R = int(sum(rows))
+    offsets = np.concatenate([[0], np.cumsum(rows)]).astype(np.int32)
+    xp = rand_bits(rng, (R, d), 1.0)
+    W1, W3, W2 = rand_bits(rng, (E, f, d), 0.05), rand_bits(rng, (E, f, d), 0.05), rand_bits(rng, (E, d, f), 0.05)
+    want = ref.expert_ffn(xp, offsets, W1, W3, W2)
+
+    ctx = B.MoeContext(R, d, f, E, 1)
+    B.moe_set_gemm_config(config)
+    try:
+        yp = torch.full((R, d), float("nan"), dtype=torch.bfloat16, device="cuda")
+        B.moe_expert_ffn(ctx, dev(bf16_tensor_from_bits(xp)), dev(offsets), R,
+                         dev(bf16_tensor_from_bits(W1)), dev(bf16_tensor_from_bits(W3)),
+                         dev(bf16_tensor_from_bits(W2)), yp)
+        torch.cuda.synchronize()
+    finally:
+        B.moe_set_gemm_config(-1)
+    got = bits(yp)
+    assert not np.isnan(bf16_to_f64(got)).any()
+    assert_close_ffn(got, want, f"expert_ffn cfg{config}")
+    ctx.close()
+
+
+def test_expert_ffn_configs_agree_bitwise():
+    """Every tile configuration runs the same accumulation chain per output element."""
+    rng = np.random.default_rng(123)
+    d, f, rows = 512, 512, [200, 3, 0, 130]
+    E, R = len(rows), sum(rows)
+    offsets = np.concatenate([[0], np.cumsum(rows)]).astype(np.int32)
+    xp = dev(bf16_tensor_from_bits(rand_bits(rng, (R, d), 1.0)))
+    W1, W3, W2 = (dev(bf16_tensor_from_bits(rand_bits(rng, s, 0.05))) for s in ((E, f, d), (E, f, d), (E, d, f)))
+    ctx = B.MoeContext(R, d, f, E, 1)
+    outs = []
+    try:
+        for config in (0, 1, 2):
+            B.moe_set_gemm_config(config)
+            yp = torch.empty((R, d), dtype=torch.bfloat16, device="cuda")
+            B.moe_expert_ffn(ctx, xp, dev(offsets), R, W1, W3, W2, yp)
+            torch.cuda.synchronize()
+            outs.append(bits(yp))
+    finally:
+        B.moe_set_gemm_config(-1)
+    assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
+    ctx.close()
+
+
+@pytest.mark.parametrize("T,d,k", [(1, 512, 1), (50, 512, 2), (33, 1024, 3), (256, 4096, 2)])
+def test_combine_parity(T, d, k):
+    say(f"combine T={T} d={d} k={k}")
+    rng = np.random.default_rng(T + d + k)
+    yp = rand_bits(rng, (T * k, d), 1.0)
+    inv = rng.permutation(T * k).astype(np.int32)
+    g = rng.random(size=(T, k)).astype(np.float32)
+    want = ref.combine(yp, inv, g)
+    ctx = B.MoeContext(T, d, 256, max(k, 2), k)
+    y = torch.empty((T, d), dtype=torch.bfloat16, device="cuda")
+    B.moe_combine(ctx, dev(bf16_tensor_from_bits(yp)), dev(inv), dev(g), T, y)
+    torch.cuda.synchronize()
+    got = bf16_to_f64(bits(y))
+    # one rounding to bf16 of an fp32 sum of k products: relative error <= 2^-8 (+ fp32 noise)
+    assert np.all(np.abs(got - want) <= 2.0 ** -8 * np.abs(want) + 1e-6 * np.abs(want).max())
+    ctx.close()
+
+
+# ----------------------------------------------------------------------------- whole layer
+def run_layer(cfg, L, T=None, micro=None, ctx=None):
+    T = cfg.T if T is None else T
+    own = ctx is None
+    if own:
+        ctx = B.MoeContext(cfg.T, cfg.d_model, cfg.d_ff, cfg.E, cfg.k)
+    y = torch.empty((T, cfg.d_model), dtype=torch.bfloat16, device="cuda")
+    args = (ctx, L["x"][:T].contiguous(), L["w_router"], L["bias"], L["W1"], L["W3"], L["W2"], T)
+    if micro is None:
+        B.moe_layer_forward(*args, y)
+    else:
+        B.moe_layer_forward_microbatched(*args, micro, y)
+    torch.cuda.synchronize()
+    return y, ctx
+
+
+def fetch_routing(ctx, T):
+    R = T * ctx.k
+    out = {"topk_idx": torch.empty((T, ctx.k), dtype=torch.int32, device="cuda"),
+           "topk_w": torch.empty((T, ctx.k), dtype=torch.float32, device="cuda"),
+           "counts": torch.empty(ctx.E, dtype=torch.int32, device="cuda"),
+           "offsets": torch.empty(ctx.E + 1, dtype=torch.int32, device="cuda"),
+           "perm": torch.empty(R, dtype=torch.int32, device="cuda"),
+           "inv_perm": torch.empty(R, dtype=torch.int32, device="cuda")}
+    B.moe_last_routing(ctx, T, **out)
+    torch.cuda.synchronize()
+    return {n: t.cpu().numpy() for n, t in out.items()}
+
+
+def host_layer(L):
+    return {"x": bits(L["x"]), "w_router": L["w_router"].cpu().numpy(),
+            "bias": None if L["bias"] is None else L["bias"].cpu().numpy(),
+            "W1": bits(L["W1"]), "W3": bits(L["W3"]), "W2": bits(L["W2"])}
+
+
+def check_routing_exact(cfg, Hh, routing, T):
+    lg = ref.logits(Hh["x"][:T], Hh["w_router"], Hh["bias"])
+    idx_ref, g_ref = ref.topk(lg, cfg.k)
+    c_ref, o_ref, p_ref, i_ref = ref.permute(idx_ref, cfg.E)
+    assert np.array_equal(routing["topk_idx"], idx_ref)
+    assert np.max(np.abs(routing["topk_w"] - g_ref)) <= GATE_TOL
+    assert np.array_equal(routing["counts"], c_ref) and np.array_equal(routing["offsets"], o_ref)
+    assert np.array_equal(routing["perm"], p_ref) and np.array_equal(routing["inv_perm"], i_ref)
+    assert int(c_ref.sum()) == T * cfg.k
+    return idx_ref, o_ref, p_ref
+
+
+def sample_tokens(cfg, offsets, perm, per_expert, seed):
+    """Tokens covering, for every non-empty expert, the first and last row of its group (tile
+    tails) and a seeded random handful of rows in between."""
+    rng = np.random.default_rng(seed)
+    rows = []
+    for e in range(cfg.E):
+        lo, hi = int(offsets[e]), int(offsets[e + 1])
+        if hi == lo:
+            continue
+        pick = {lo, hi - 1}
+        pick.update(int(v) for v in rng.integers(lo, hi, size=per_expert))
+        rows.extend(sorted(pick))
+    return np.unique(perm[np.array(rows)] // cfg.k).astype(np.int32)
+
+
+def test_layer_tiny_all_tokens():
+    cfg = synth.PRESETS["tiny"]
+    say("layer tiny: all tokens, coalesced + micro-batched")
+    L = synth.make_layer(cfg, "cuda")
+    Hh = host_layer(L)
+    y, ctx = run_layer(cfg, L)
+    routing = fetch_routing(ctx, cfg.T)
+    check_routing_exact(cfg, Hh, routing, cfg.T)
+    want, _, _ = ref.layer_tokens(Hh["x"], Hh["w_router"], None, Hh["W1"], Hh["W3"], Hh["W2"], cfg.k)
+    assert_close_ffn(bits(y), want, "tiny layer")
+    for m in (64, 100, 1, 256, 1000):
+        ym, _ = run_layer(cfg, L, micro=m, ctx=ctx)
+        assert torch.equal(ym.view(torch.int16), y.view(torch.int16)), f"micro m={m} differs"
+    # determinism: the same call twice gives the same bits
+    y2, _ = run_layer(cfg, L, ctx=ctx)
+    assert torch.equal(y2.view(torch.int16), y.view(torch.int16))
+    ctx.close()
+
+
+@pytest.mark.parametrize("T", [1, 2, 63, 65, 255])
+def test_layer_tiny_ragged_T(T):
+    cfg = synth.PRESETS["tiny"]
+    say(f"layer tiny T={T}")
+    L = synth.make_layer(cfg, "cuda")
+    Hh = host_layer(L)
+    y, ctx = run_layer(cfg, L, T=T)
+    check_routing_exact(cfg, Hh, fetch_routing(ctx, T), T)
+    want, _, _ = ref.layer_tokens(Hh["x"], Hh["w_router"], None, Hh["W1"], Hh["W3"], Hh["W2"], cfg.k,
+                                  tokens=np.arange(T, dtype=np.int32))
+    assert_close_ffn(bits(y), want, f"tiny T={T}")
+    ctx.close()
+
+
+def test_layer_T0_and_errors():
+    cfg = synth.PRESETS["tiny"]
+    L = synth.make_layer(cfg, "cuda")
+    ctx = B.MoeContext(cfg.T, cfg.d_model, cfg.d_ff, cfg.E, cfg.k)
+    y = torch.zeros((1, cfg.d_model), dtype=torch.bfloat16, device="cuda")
+    B.moe_layer_forward(ctx, L["x"], L["w_router"], None, L["W1"], L["W3"], L["W2"], 0, y)   # no-op
+    with pytest.raises(B.MoeError):
+        B.moe_layer_forward(ctx, L["x"], L["w_router"], None, L["W1"], L["W3"], L["W2"], cfg.T + 1, y)
+    with pytest.raises(B.MoeError):
+        B.moe_layer_forward(ctx, None, L["w_router"], None, L["W1"], L["W3"], L["W2"], 4, y)
+    with pytest.raises(B.MoeError):
+        B.moe_layer_forward_microbatched(ctx, L["x"], L["w_router"], None, L["W1"], L["W3"], L["W2"], 4, 0, y)
+    with pytest.raises(B.MoeError):
+        B.MoeContext(16, 500, 1024, 8, 2)
+    torch.cuda.synchronize()
+    ctx.close()
+
+
+def test_layer_mixtral8x7b_decode():
+    cfg = synth.PRESETS["mixtral8x7b_decode"]
+    say("layer 8x7B decode: routing all tokens, FFN on sampled tokens")
+    L = synth.make_layer(cfg, "cuda")
+    Hh = host_layer(L)
+    y, ctx = run_layer(cfg, L)
+    routing = fetch_routing(ctx, cfg.T)
+    _, o_ref, p_ref = check_routing_exact(cfg, Hh, routing, cfg.T)
+    say(f"    rows per expert {routing['counts'].tolist()}")
+    tokens = sample_tokens(cfg, o_ref, p_ref, 6, 1)
+    want, _, _ = ref.layer_tokens(Hh["x"], Hh["w_router"], None, Hh["W1"], Hh["W3"], Hh["W2"], cfg.k, tokens)
+    assert_close_ffn(bits(y)[tokens], want, f"8x7B decode ({tokens.size} tokens)")
+    ctx.close()
+
+
+@pytest.fixture(scope="module")
+def experts_8x22b():
+    """One set of Mixtral-8x22B-shaped expert weights shared by the 8x22B cases (their token
+    and router seeds still differ per case)."""
+    cfg = synth.PRESETS["mixtral8x22b_prefill"]
+    say("generating 8x22B-shaped expert weights on the GPU")
+    W1, W3, W2 = synth.make_experts(cfg, "cuda")
+    host = tuple(bits(w) for w in (W1, W3, W2))
+    return (W1, W3, W2), host
+
+
+def layer_8x22b(cfg, experts):
+    (W1, W3, W2), (h1, h3, h2) = experts
+    L = {"x": synth.make_tokens(cfg, "cuda"), "w_router": synth.make_router(cfg, "cuda"), "bias": None,
+         "W1": W1, "W3": W3, "W2": W2}
+    Hh = {"x": bits(L["x"]), "w_router": L["w_router"].cpu().numpy(), "bias": None,
+          "W1": h1, "W3": h3, "W2": h2}
+    return L, Hh
+
+
+def test_layer_mixtral8x22b_prefill(experts_8x22b):
+    cfg = synth.PRESETS["mixtral8x22b_prefill"]
+    say("layer 8x22B prefill T=8192")
+    L, Hh = layer_8x22b(cfg, experts_8x22b)
+    y, ctx = run_layer(cfg, L)
+    routing = fetch_routing(ctx, cfg.T)
+    _, o_ref, p_ref = check_routing_exact(cfg, Hh, routing, cfg.T)
+    say(f"    rows per expert {routing['counts'].tolist()}")
+    tokens = sample_tokens(cfg, o_ref, p_ref, 10, 2)
+    want, _, _ = ref.layer_tokens(Hh["x"], Hh["w_router"], None, Hh["W1"], Hh["W3"], Hh["W2"], cfg.k, tokens)
+    assert_close_ffn(bits(y)[tokens], want, f"8x22B prefill ({tokens.size} tokens)")
+    ctx.close()
+
+
+def test_layer_mixtral8x22b_coalesced_vs_microbatched(experts_8x22b):
+    cfg = synth.PRESETS["mixtral8x22b_coalesce"]
+    say(f"layer 8x22B T={cfg.T}: coalesced vs {cfg.T // cfg.micro_tokens} micro-batches of {cfg.micro_tokens}")
+    L, Hh = layer_8x22b(cfg, experts_8x22b)
+    y, ctx = run_layer(cfg, L)
+    routing = fetch_routing(ctx, cfg.T)
+    _, o_ref, p_ref = check_routing_exact(cfg, Hh, routing, cfg.T)
+    ym, _ = run_layer(cfg, L, micro=cfg.micro_tokens, ctx=ctx)
+    assert torch.equal(ym.view(torch.int16), y.view(torch.int16)), "micro-batched output differs"
+    tokens = sample_tokens(cfg, o_ref, p_ref, 4, 3)
+    want, _, _ = ref.layer_tokens(Hh["x"], Hh["w_router"], None, Hh["W1"], Hh["W3"], Hh["W2"], cfg.k, tokens)
+    assert_close_ffn(bits(y)[tokens], want, f"8x22B coalesced ({tokens.size} tokens)")
+    ctx.close()
+
+
+@pytest.mark.parametrize("preset", ["mixtral8x22b_zipf", "mixtral8x22b_zipf_empty"])
+def test_layer_mixtral8x22b_zipf(experts_8x22b, preset):
+    cfg = synth.PRESETS[preset]
+    say(f"layer {preset} T={cfg.T}")
+    L, Hh = layer_8x22b(cfg, experts_8x22b)
+    base = ref.logits(Hh["x"], Hh["w_router"])
+
+    def count_fn(bias):                       # calibration runs on the oracle's router
+        idx, _ = ref.topk(base + bias.numpy()[None, :], cfg.k)
+        return np.bincount(idx.reshape(-1), minlength=cfg.E)
+
+    bias = synth.calibrate_expert_bias(cfg, count_fn)
+    L["bias"], Hh["bias"] = bias.cuda(), bias.numpy()
+    y, ctx = run_layer(cfg, L)
+    routing = fetch_routing(ctx, cfg.T)
+    _, o_ref, p_ref = check_routing_exact(cfg, Hh, routing, cfg.T)
+    counts = routing["counts"]
+    say(f"    rows per expert {counts.tolist()}")
+    target = synth.zipf_target_counts(cfg).numpy()
+    live = target > 0
+    assert np.all(np.abs(counts[live] - target[live]) <= 0.02 * target[live])
+    assert (counts[~live] == 0).all() and (~live).sum() == (1 if cfg.empty_expert else 0)
+    tokens = sample_tokens(cfg, o_ref, p_ref, 4, 4)
+    want, _, _ = ref.layer_tokens(Hh["x"], Hh["w_router"], Hh["bias"], Hh["W1"], Hh["W3"], Hh["W2"], cfg.k, tokens)
+    assert_close_ffn(bits(y)[tokens], want, f"{preset} ({tokens.size} tokens)")
+    ctx.close()
