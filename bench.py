@@ -1,0 +1,181 @@
+#!/usr/bin/env python3
+"""Benchmark of the coalesced MoE-layer hot path on one MI355X.
+
+A step is one pass of the whole path (route -> permute -> gather -> gate/up GEMM -> down GEMM
+-> combine) over one batch of synthetic tokens already resident in HBM. The default workload
+is the Mixtral-8x22B-shaped prefill chunk (T=8192, d=6144, f=16384, E=8, k=2). Prints ONE
+JSON line: whole-layer tokens/s, the roofline of the dominant kernel (the gate/up grouped
+GEMM, measured with HIP events on the launch stream inside the timed region), per-stage
+figures, and the CPU oracle timed on the host cores on a bounded token sample.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--micro M]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA peak
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E peak
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def stage_model(cfg, T, calls_per_step):
+    """Algorithmic work of each stage for ONE layer call over T tokens (bytes or FLOPs)."""
+    d, f, E, k = cfg.d_model, cfg.d_ff, cfg.E, cfg.k
+    R = T * k
+    return {
+        "route": {"bound": "hbm", "bytes": T * (2 * d + 8 * k)},
+        "permute": {"bound": "latency", "bytes": T * (4 * k + 8 * k)},
+        "gather": {"bound": "hbm", "bytes": T * 2 * d + R * 2 * d},
+        "gateup": {"bound": "mfma", "flops": 4 * R * d * f,
+                   "bytes": 4 * d * f * E * calls_per_step + R * 2 * d + R * 2 * f},
+        "down": {"bound": "mfma", "flops": 2 * R * d * f,
+                 "bytes": 2 * d * f * E * calls_per_step + R * 2 * f + R * 2 * d},
+        "combine": {"bound": "hbm", "bytes": R * 2 * d + T * 2 * d},
+    }
+
+
+def cpu_baseline(cfg, L, target_seconds=15.0):
+    """The oracle as it stands, timed on this machine's host cores on a seeded token sample."""
+    import numpy as np
+    from oracle import ref
+    from paper_2605_17889_amd import synth
+
+    host = {n: synth.bf16_bits(L[n]) for n in ("x", "W1", "W3", "W2")}
+    wr = L["w_router"].cpu().numpy()
+    bias = None if L["bias"] is None else L["bias"].cpu().numpy()
+    rng = np.random.default_rng(12345)
+    threads = ref.num_threads()
+
+    def run(n):
+        tokens = np.sort(rng.choice(cfg.T, size=n, replace=False)).astype(np.int32)
+        t0 = time.perf_counter()
+        ref.layer_tokens(host["x"], wr, bias, host["W1"], host["W3"], host["W2"], cfg.k, tokens)
+        return time.perf_counter() - t0
+
+    probe = min(cfg.T, 4 * threads)
+    dt = run(probe)
+    n = int(max(probe, min(cfg.T, 2048, probe * target_seconds / max(dt, 1e-3))))
+    if n > probe:
+        dt = run(n)
+    return {"value": n / dt, "unit": "tokens/s", "cores": threads, "kind": "oracle",
+            "sample": f"{n} seeded tokens of the same {cfg.name} batch (tokens are independent in "
+                      f"the oracle), {dt:.2f} s wall, double precision, OpenMP over tokens"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="mixtral8x22b_prefill")
+    ap.add_argument("--micro", type=int, default=0,
+                    help="run the micro-batched call with this many tokens per micro-batch")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
+            "use --gpus 1")
+        sys.exit(2)
+
+    import torch
+    from paper_2605_17889_amd import binding as B
+    from paper_2605_17889_amd import synth
+
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible; the HIP path has no CPU fallback")
+        sys.exit(3)
+    cfg = synth.PRESETS[args.workload]
+    T = cfg.T
+    log(f"[bench] generating {cfg.name}: T={T} d={cfg.d_model} f={cfg.d_ff} E={cfg.E} k={cfg.k}")
+    L = synth.make_layer(cfg, "cuda")
+    ctx = B.MoeContext(T, cfg.d_model, cfg.d_ff, cfg.E, cfg.k)
+    if cfg.zipf_s is not None:
+        idx = torch.empty((T, cfg.k), dtype=torch.int32, device="cuda")
+        w = torch.empty((T, cfg.k), dtype=torch.float32, device="cuda")
+
+        def count_fn(bias):
+            B.moe_route(ctx, L["x"], L["w_router"], bias.cuda(), T, idx, w)
+            return torch.bincount(idx.view(-1).long(), minlength=cfg.E).cpu().tolist()
+
+        L["bias"] = synth.calibrate_expert_bias(cfg, count_fn).cuda()
+    y = torch.empty((T, cfg.d_model), dtype=torch.bfloat16, device="cuda")
+
+    def step():
+        if args.micro > 0:
+            B.moe_layer_forward_microbatched(ctx, L["x"], L["w_router"], L["bias"], L["W1"], L["W3"],
+                                             L["W2"], T, args.micro, y)
+        else:
+            B.moe_layer_forward(ctx, L["x"], L["w_router"], L["bias"], L["W1"], L["W3"], L["W2"], T, y)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    B.moe_profile_begin(ctx, args.steps)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    stage_ms, launches, calls = B.moe_profile_end(ctx)
+    counts = torch.empty(cfg.E, dtype=torch.int32, device="cuda")
+    B.moe_last_routing(ctx, min(T, args.micro) if args.micro > 0 else T, counts=counts)
+    torch.cuda.synchronize()
+
+    ms_per_step = elapsed / args.steps * 1e3
+    chunks = (T + args.micro - 1) // args.micro if args.micro > 0 else 1
+    model = stage_model(cfg, T, chunks)
+    stages = {}
+    for name in B.STAGES:
+        ms = stage_ms[name] / max(calls, 1)
+        n_launch = launches[name] / max(calls, 1)
+        ent = {"ms_per_step": ms, "launches_per_step": n_launch, "bound": model[name]["bound"]}
+        if ms > 0:
+            ent["GB/s"] = model[name]["bytes"] / (ms * 1e-3) / 1e9
+            if "flops" in model[name]:
+                ent["TFLOP/s"] = model[name]["flops"] / (ms * 1e-3) / 1e12
+        stages[name] = ent
+    gemm_ms = stages["gateup"]["ms_per_step"] + stages["down"]["ms_per_step"]
+    gemm_tflops = synth.expert_ffn_flops(T * cfg.k, cfg.d_model, cfg.d_ff) / (gemm_ms * 1e-3) / 1e12
+
+    dom = stages["gateup"]
+    dom_launch_ms = dom["ms_per_step"] / max(dom["launches_per_step"], 1)
+    dom_flops_per_launch = model["gateup"]["flops"] / max(dom["launches_per_step"], 1)
+    achieved = dom_flops_per_launch / (dom_launch_ms * 1e-3) / 1e12
+    roofline = {"kernel": "grouped_gemm_kernel<gate/up, fused SiLU*mul>", "bound": "mfma",
+                "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                "avg_launch_ms": dom_launch_ms,
+                "algorithmic_flops_per_launch": dom_flops_per_launch}
+
+    out = {
+        "metric": "MoE-layer tokens/sec and expert-GEMM TFLOP/s (% bf16 MFMA peak), 8x22B shape",
+        "value": T / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": cfg.name, "T": T, "d_model": cfg.d_model, "d_ff": cfg.d_ff, "E": cfg.E,
+                   "k": cfg.k, "micro_tokens": args.micro or None,
+                   "rows_per_expert_last_call": counts.cpu().tolist()},
+        "expert_gemm_TFLOP/s": gemm_tflops,
+        "expert_gemm_frac_of_bf16_peak": gemm_tflops / PEAK_BF16_TFLOPS,
+        "roofline": roofline,
+        "stages": stages,
+    }
+    if not args.no_cpu_baseline:
+        log("[bench] timing the CPU oracle on a token sample")
+        out["cpu_baseline"] = cpu_baseline(cfg, L)
+    ctx.close()
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

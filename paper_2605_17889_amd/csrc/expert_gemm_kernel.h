@@ -1,0 +1,288 @@
+// Grouped expert GEMM kernel for gfx950 (device code; included by expert_gemm.hip).
+//
+//   C[p, n] = sum_k A[p, k] * B_e[n, k]           for the rows p of expert e's group,
+// both operands contiguous along k ("NT"), bf16 in, fp32 accumulation on
+// v_mfma_f32_32x32x16_bf16, bf16 out. With DUAL, a tile carries BN/2 rows of W1 and the
+// matching BN/2 rows of W3 (interleaved in blocks of 32) and stores SiLU(gate)*up.
+//
+// Data path: global memory -> LDS by direct-to-LDS loads (no VGPR staging), a ring of NSTAGE
+// LDS stages, one workgroup barrier per k-step; LDS -> VGPR by 16-byte reads of a swizzled
+// layout; MFMA. Tiles are enumerated on the device from `offsets`.
+#pragma once
+#include "common.h"
+
+namespace moe {
+namespace gemm {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kXcds = 8;     // workgroups are dealt round-robin to the 8 XCDs (own L2 each)
+constexpr int kGroupM = 8;   // m-tiles that sweep the n-tiles together (share weight tiles)
+
+struct TileCoord {
+    int expert;      // -1: no tile for this workgroup
+    int row0;        // first row (in the permuted matrix) of the tile
+    int rows;        // valid rows in the tile (1..BM)
+    int nt;          // n-tile index
+};
+
+// Map a workgroup to its tile. Logical tile order: expert by expert; inside an expert, groups
+// of kGroupM m-tiles; inside a group the n-tiles, each visited by all m-tiles of the group in
+// turn. XCD x is handed the x-th contiguous eighth of that order, so the workgroups resident
+// together on one XCD share A rows and weight tiles in its L2.
+template <int BM>
+__device__ __forceinline__ TileCoord locate_tile(const int32_t* __restrict__ offsets, int E,
+                                                 int NT) {
+    TileCoord tc{-1, 0, 0, 0};
+    int total = 0;
+    for (int e = 0; e < E; ++e) total += ((offsets[e + 1] - offsets[e] + BM - 1) / BM) * NT;
+    const int per = (total + kXcds - 1) / kXcds;
+    const int xcd = blockIdx.x % kXcds;
+    const int slot = blockIdx.x / kXcds;
+    const int L = xcd * per + slot;
+    if (slot >= per || L >= total) return tc;
+    int start = 0;
+    for (int e = 0; e < E; ++e) {
+        const int m_e = offsets[e + 1] - offsets[e];
+        const int mt = (m_e + BM - 1) / BM;
+        const int n_tiles = mt * NT;
+        if (L < start + n_tiles) {
+            const int local = L - start;
+            const int g = local / (kGroupM * NT);
+            const int first = g * kGroupM;
+            const int gm = min(kGroupM, mt - first);
+            const int in = local - g * (kGroupM * NT);
+            const int mi = first + in % gm;
+            tc.expert = e;
+            tc.nt = in / gm;
+            tc.row0 = offsets[e] + mi * BM;
+            tc.rows = min(BM, m_e - mi * BM);
+            return tc;
+        }
+        start += n_tiles;
+    }
+    return tc;
+}
+
+// LDS tile layout: rows of BK bf16 in 16-byte chunks; logical chunk c of row r is stored at
+// chunk position c ^ swz(r). LDS has 64 four-byte banks and a 16-byte read is served 16 lanes
+// at a time, so the swizzle makes any 16 consecutive rows at one logical chunk hit 16 distinct
+// 16-byte slots of a 256-byte bank window.
+template <int BK>
+__device__ __forceinline__ int swz(int row) {
+    if (BK == 64) return (row >> 1) & 7;     // 128-byte rows: 2 rows per bank window
+    return (row >> 2) & 3;                   // 64-byte rows: 4 rows per bank window
+}
+
+// One direct-to-LDS load: every lane fetches 16 bytes from sbase + voff and the wavefront's
+// 64 x 16 bytes land contiguously at LDS byte offset lds_off (wave-uniform, passed in M0).
+// The compiler is not told that this is a memory operation with a counter: the kernel places
+// its own s_waitcnt vmcnt(n) before the barrier that publishes a stage.
+__device__ __forceinline__ void dma16(const void* sbase, uint32_t voff, uint32_t lds_off) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(lds_off), "v"(voff), "s"(sbase) : "memory", "m0");
+}
+
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+    static_assert(N >= 0 && N < 64, "vmcnt range");
+    asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
+}
+
+__device__ __forceinline__ float silu(float a) { return a / (1.0f + __expf(-a)); }
+
+__device__ __forceinline__ uint16_t to_bf16(float v) {
+    __bf16 h = static_cast<__bf16>(v);       // v_cvt_pk_bf16_f32: round to nearest even
+    return *reinterpret_cast<uint16_t*>(&h);
+}
+
+template <int BM_, int BN_, int BK_, int WM_, int WN_, int NSTAGE_, bool DUAL_>
+struct Config {
+    static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_, NSTAGE = NSTAGE_;
+    static constexpr bool DUAL = DUAL_;
+    static constexpr int NW = WM * WN, NTHREADS = NW * 64;
+    static constexpr int WTM = BM / WM, WTN = BN / WN, TM = WTM / 32, TN = WTN / 32;
+    static constexpr int CPR = BK / 8;                     // 16-byte chunks per row
+    static constexpr int RPI = 64 / CPR;                   // rows one wavefront load covers
+    static constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
+    static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
+    static constexpr int SMEM = NSTAGE * STAGE_BYTES;
+    static constexpr int NIA = BM / RPI, NIB = BN / RPI;   // wavefront loads per stage
+    static constexpr int LPW = (NIA + NIB) / NW;           // ... per wavefront
+    static constexpr int BN_OUT = DUAL ? BN / 2 : BN;      // output columns per tile
+    static_assert(BK == 64 || BK == 32, "BK");
+    static_assert(BM % (WM * 32) == 0 && BN % (WN * 32) == 0, "wave tile");
+    static_assert(!DUAL || TN % 2 == 0, "gate/up pairs must live in one wave");
+    static_assert(NIA % NW == 0 && NIB % NW == 0, "loads must split evenly over wavefronts");
+    static_assert(NSTAGE >= 2 && SMEM <= 160 * 1024, "LDS budget");
+};
+
+template <class Cfg>
+__global__ __launch_bounds__(Cfg::NTHREADS) void grouped_gemm_kernel(
+    const uint16_t* __restrict__ A, const uint16_t* __restrict__ B0,
+    const uint16_t* __restrict__ B1, uint16_t* __restrict__ C,
+    const int32_t* __restrict__ offsets, int E, int N, int K) {
+    constexpr int BM = Cfg::BM, BK = Cfg::BK, WN = Cfg::WN, NW = Cfg::NW;
+    constexpr int WTM = Cfg::WTM, WTN = Cfg::WTN, TM = Cfg::TM, TN = Cfg::TN;
+    constexpr int CPR = Cfg::CPR, RPI = Cfg::RPI, NIA = Cfg::NIA, NIB = Cfg::NIB;
+    constexpr int LA = NIA / NW, LB = NIB / NW, LPW = Cfg::LPW, NSTAGE = Cfg::NSTAGE;
+    constexpr int BN_OUT = Cfg::BN_OUT;
+    constexpr bool DUAL = Cfg::DUAL;
+
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+
+    const TileCoord tc = locate_tile<BM>(offsets, E, N / BN_OUT);
+    if (tc.expert < 0) return;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WN, wn = wave % WN;
+
+    // ---- direct-to-LDS load plan. Wavefront load q of a stage covers tile rows
+    //      [q*RPI, (q+1)*RPI); lane l lands at row q*RPI + l/CPR, chunk position l%CPR, so it
+    //      must fetch logical chunk (l%CPR) ^ swz(row). A rows past the group's end are
+    //      clamped to its last row (always in bounds; masked at the store).
+    const int lrow = lane / CPR, lpos = lane % CPR;
+    const uint16_t* a_base = A + static_cast<size_t>(tc.row0) * K;   // wave-uniform
+    uint32_t a_voff[LA];
+    uint32_t a_lds[LA];
+#pragma unroll
+    for (int i = 0; i < LA; ++i) {
+        const int q = wave * LA + i;
+        const int r = q * RPI + lrow;
+        const int rr = min(r, tc.rows - 1);
+        a_voff[i] = (static_cast<uint32_t>(rr) * K + ((lpos ^ swz<BK>(r)) * 8)) * 2u;
+        a_lds[i] = q * 1024;
+    }
+    const uint16_t* b_base[LB];
+    uint32_t b_voff[LB];
+    uint32_t b_lds[LB];
+#pragma unroll
+    for (int i = 0; i < LB; ++i) {
+        const int q = wave * LB + i;
+        const int r0 = q * RPI;                       // wave-uniform first tile row
+        const int r = r0 + lrow;
+        int col0;                                     // weight row of tile row r0
+        const uint16_t* base;
+        if (DUAL) {
+            const int b32 = r0 >> 5;
+            col0 = tc.nt * BN_OUT + (b32 >> 1) * 32 + (r0 & 31);
+            base = (b32 & 1) ? B1 : B0;
+        } else {
+            col0 = tc.nt * BN_OUT + r0;
+            base = B0;
+        }
+        b_base[i] = base + (static_cast<size_t>(tc.expert) * N + col0) * K;
+        b_voff[i] = (static_cast<uint32_t>(lrow) * K + ((lpos ^ swz<BK>(r)) * 8)) * 2u;
+        b_lds[i] = Cfg::A_BYTES + q * 1024;
+    }
+
+    auto issue = [&](int stage, int kt) {
+        const uint32_t sbase = stage * Cfg::STAGE_BYTES;
+        const size_t koff = static_cast<size_t>(kt) * BK;
+#pragma unroll
+        for (int i = 0; i < LA; ++i) dma16(a_base + koff, a_voff[i], sbase + a_lds[i]);
+#pragma unroll
+        for (int i = 0; i < LB; ++i) dma16(b_base[i] + koff, b_voff[i], sbase + b_lds[i]);
+    };
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.f;
+
+    const int frag_row = lane & 31;      // operand row inside a 32-row MFMA tile
+    const int frag_half = lane >> 5;     // which 8 of the 16 k this lane feeds
+
+    // per-lane LDS byte offsets of the operand fragments for k-substep 0 (others: xor below)
+    int a_off[TM], b_off[TN];
+    int a_sw[TM], b_sw[TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int r = wm * WTM + i * 32 + frag_row;
+        a_off[i] = r * (BK * 2);
+        a_sw[i] = swz<BK>(r);
+    }
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int r = wn * WTN + j * 32 + frag_row;
+        b_off[j] = Cfg::A_BYTES + r * (BK * 2);
+        b_sw[j] = swz<BK>(r);
+    }
+
+    auto compute = [&](int stage) {
+        const unsigned char* s = smem + stage * Cfg::STAGE_BYTES;
+#pragma unroll
+        for (int kk = 0; kk < BK / 16; ++kk) {
+            bf16x8 af[TM], bfr[TN];
+            const int c = kk * 2 + frag_half;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+                af[i] = *reinterpret_cast<const bf16x8*>(s + a_off[i] + ((c ^ a_sw[i]) << 4));
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                bfr[j] = *reinterpret_cast<const bf16x8*>(s + b_off[j] + ((c ^ b_sw[j]) << 4));
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+        }
+    };
+
+    // ---- main loop: ring of NSTAGE stages, NSTAGE-1 k-steps of loads in flight.
+    const int KT = K / BK;
+#pragma unroll
+    for (int s = 0; s < NSTAGE - 1; ++s)
+        if (s < KT) issue(s, s);
+    int stage = 0;
+    for (int kt = 0; kt < KT; ++kt) {
+        // The loads of k-step kt are the oldest in flight; up to NSTAGE-2 newer steps may stay
+        // pending. Near the tail fewer are in flight, so wait for everything.
+        if (kt + NSTAGE - 2 < KT) wait_vmcnt<(NSTAGE - 2) * LPW>(); else wait_vmcnt<0>();
+        __builtin_amdgcn_s_barrier();          // stage `stage` is complete for every wavefront
+                                               // and stage (stage-1) is no longer being read
+        const int nk = kt + NSTAGE - 1;
+        if (nk < KT) issue(stage == 0 ? NSTAGE - 1 : stage - 1, nk);
+        compute(stage);
+        stage = (stage + 1 == NSTAGE) ? 0 : stage + 1;
+    }
+
+    // ---- epilogue. MFMA 32x32 result layout: lane holds column (lane & 31); register 4*q + r
+    //      is row 8*q + 4*(lane >> 5) + r.
+    const int ldc = N;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+        for (int j = 0; j < TN; j += (DUAL ? 2 : 1)) {
+            int col;
+            if (DUAL) {
+                const int b32 = (wn * WTN) / 32 + j;
+                col = tc.nt * BN_OUT + (b32 >> 1) * 32 + frag_row;
+            } else {
+                col = tc.nt * BN_OUT + wn * WTN + j * 32 + frag_row;
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int row = wm * WTM + i * 32 + 8 * q + 4 * frag_half + r;
+                    if (row < tc.rows) {
+                        float v;
+                        if (DUAL) v = silu(acc[i][j][4 * q + r]) * acc[i][j + (DUAL ? 1 : 0)][4 * q + r];
+                        else v = acc[i][j][4 * q + r];
+                        C[static_cast<size_t>(tc.row0 + row) * ldc + col] = to_bf16(v);
+                    }
+                }
+        }
+    }
+}
+
+}  // namespace gemm
+}  // namespace moe
