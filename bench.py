@@ -23,6 +23,12 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA peak
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E peak
 
+# Bytes one launch of the gate/up kernel moves past L2 (rocprofv3 FETCH_SIZE + WRITE_SIZE, each
+# scaled by what the same counter reads for a plain 1 GiB copy: 2.00 and 1.00). Measured with the
+# commands recorded in profiles/expert_gemm_mixtral8x22b_prefill_hbm_traffic.md; it cannot be
+# measured from inside this process, so workloads without a recorded value report null.
+MEASURED_TRAFFIC_BYTES = {"mixtral8x22b_prefill": 11.36e9 + 0.537e9}
+
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
@@ -75,12 +81,15 @@ def cpu_baseline(cfg, L, target_seconds=15.0):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="mixtral8x22b_prefill")
     ap.add_argument("--micro", type=int, default=0,
                     help="run the micro-batched call with this many tokens per micro-batch")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a plain 1 GiB device copy 10 times (to scale rocprofv3's "
+                         "FETCH_SIZE / WRITE_SIZE counters against a kernel of known traffic)")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
@@ -94,6 +103,15 @@ def main():
     if not torch.cuda.is_available():
         log("bench.py: no GPU visible; the HIP path has no CPU fallback")
         sys.exit(3)
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": {"bytes_read": 1 << 30, "bytes_written": 1 << 30,
+                                               "launches": 10}}), flush=True)
+        return
     cfg = synth.PRESETS[args.workload]
     T = cfg.T
     log(f"[bench] generating {cfg.name}: T={T} d={cfg.d_model} f={cfg.d_ff} E={cfg.E} k={cfg.k}")
@@ -153,7 +171,8 @@ def main():
     achieved = dom_flops_per_launch / (dom_launch_ms * 1e-3) / 1e12
     roofline = {"kernel": "grouped_gemm_kernel<gate/up, fused SiLU*mul>", "bound": "mfma",
                 "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                "frac": achieved / PEAK_BF16_TFLOPS,
+                "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name) if args.micro == 0 else None,
                 "avg_launch_ms": dom_launch_ms,
                 "algorithmic_flops_per_launch": dom_flops_per_launch}
 
