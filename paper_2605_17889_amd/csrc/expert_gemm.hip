@@ -17,11 +17,17 @@ namespace {
 
 using gemm::Config;
 
-template <class Cfg>
+// WS = true launches the wavefront-specialised kernel (8 consumer + 3 service wavefronts).
+template <class Cfg, bool WS = false>
 int launch_grouped(const moe_bf16* A, const moe_bf16* B0, const moe_bf16* B1, moe_bf16* C,
                    const int32_t* offsets, int R, int E, int N, int K, hipStream_t s) {
     if (N % Cfg::BN_OUT != 0 || K % Cfg::BK != 0) return MOE_ERR_UNSUPPORTED_SHAPE;
-    auto kern = gemm::grouped_gemm_kernel<Cfg>;
+    using Kernel = void (*)(const uint16_t*, const uint16_t*, const uint16_t*, uint16_t*,
+                            const int32_t*, int, int, int);
+    Kernel kern;
+    if constexpr (WS) kern = gemm::grouped_gemm_ws_kernel<Cfg>;
+    else kern = gemm::grouped_gemm_kernel<Cfg>;
+    constexpr int kThreads = Cfg::NTHREADS + (WS ? gemm::kWsExtraWaves * 64 : 0);
     static bool attr_set = false;
     if (!attr_set) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -33,7 +39,7 @@ int launch_grouped(const moe_bf16* A, const moe_bf16* B0, const moe_bf16* B1, mo
     long long grid = max_mt * (N / Cfg::BN_OUT);
     grid = (grid + gemm::kXcds - 1) / gemm::kXcds * gemm::kXcds;
     if (grid > 0x7fffffffLL) return MOE_ERR_UNSUPPORTED_SHAPE;
-    hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(grid)), dim3(Cfg::NTHREADS), Cfg::SMEM, s,
+    hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(grid)), dim3(kThreads), Cfg::SMEM, s,
                        A, B0, B1, C, offsets, E, N, K);
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
@@ -65,7 +71,7 @@ int launch_gateup(const moe_bf16* x_perm, const int32_t* offsets, int R, int d, 
                   const moe_bf16* W1, const moe_bf16* W3, moe_bf16* H, hipStream_t s) {
     if (R == 0) return MOE_OK;
     switch (pick_config(R, E)) {
-        case 0: return launch_grouped<GateUpLarge>(x_perm, W1, W3, H, offsets, R, E, f, d, s);
+        case 0: return launch_grouped<GateUpLarge, true>(x_perm, W1, W3, H, offsets, R, E, f, d, s);
         case 1: return launch_grouped<GateUpMid>(x_perm, W1, W3, H, offsets, R, E, f, d, s);
         default: return launch_grouped<GateUpSmall>(x_perm, W1, W3, H, offsets, R, E, f, d, s);
     }
@@ -75,7 +81,7 @@ int launch_down(const moe_bf16* H, const int32_t* offsets, int R, int d, int f, 
                 const moe_bf16* W2, moe_bf16* y_perm, hipStream_t s) {
     if (R == 0) return MOE_OK;
     switch (pick_config(R, E)) {
-        case 0: return launch_grouped<DownLarge>(H, W2, nullptr, y_perm, offsets, R, E, d, f, s);
+        case 0: return launch_grouped<DownLarge, true>(H, W2, nullptr, y_perm, offsets, R, E, d, f, s);
         case 1: return launch_grouped<DownMid>(H, W2, nullptr, y_perm, offsets, R, E, d, f, s);
         default: return launch_grouped<DownSmall>(H, W2, nullptr, y_perm, offsets, R, E, d, f, s);
     }
