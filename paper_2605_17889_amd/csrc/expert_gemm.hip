@@ -49,18 +49,22 @@ int g_forced_config = -1;   // -1: automatic; 0,1,2: force (tests / tuning)
 
 int pick_config(int R, int E) {
     if (g_forced_config >= 0) return g_forced_config;
+    // 0: compute-bound groups (wavefront-specialised 256x256 tiles). 1: groups of up to ~128
+    // rows: the kernel streams the weights once per 128-row m-tile and is HBM-bound. 2: a few
+    // rows per expert (64-row tiles).
     const int avg = R / (E > 0 ? E : 1);
     if (avg >= 192) return 0;
-    if (avg >= 96) return 1;
+    if (avg > 32) return 1;
     return 2;
 }
 
 //                      BM   BN  BK WM WN NSTAGE DUAL
 using GateUpLarge = Config<256, 256, 64, 2, 4, 2, true>;
-using GateUpMid   = Config<128, 128, 64, 2, 2, 3, true>;
+using GateUpMid   = Config<128, 256, 64, 2, 4, 3, true>;
 using GateUpSmall = Config<64, 128, 64, 1, 2, 4, true>;
 using DownLarge   = Config<256, 256, 64, 2, 4, 2, false>;
-using DownMid     = Config<128, 128, 64, 2, 2, 3, false>;
+using DownMid     = Config<128, 128, 64, 2, 2, 4, false>;
+using DownMidWide = Config<128, 256, 64, 2, 4, 3, false>;
 using DownSmall   = Config<64, 64, 64, 1, 2, 4, false>;
 
 }  // namespace
@@ -82,7 +86,12 @@ int launch_down(const moe_bf16* H, const int32_t* offsets, int R, int d, int f, 
     if (R == 0) return MOE_OK;
     switch (pick_config(R, E)) {
         case 0: return launch_grouped<DownLarge, true>(H, W2, nullptr, y_perm, offsets, R, E, d, f, s);
-        case 1: return launch_grouped<DownMid>(H, W2, nullptr, y_perm, offsets, R, E, d, f, s);
+        case 1:
+            // HBM-bound: wide tiles stream more bytes per workgroup, but only if there are
+            // enough of them to occupy the 256 compute units (about one m-tile per expert).
+            if (static_cast<long long>(E) * (d / 256) >= 160 && d % 256 == 0)
+                return launch_grouped<DownMidWide>(H, W2, nullptr, y_perm, offsets, R, E, d, f, s);
+            return launch_grouped<DownMid>(H, W2, nullptr, y_perm, offsets, R, E, d, f, s);
         default: return launch_grouped<DownSmall>(H, W2, nullptr, y_perm, offsets, R, E, d, f, s);
     }
 }
