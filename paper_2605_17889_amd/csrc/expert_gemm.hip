@@ -20,10 +20,11 @@ using gemm::Config;
 // WS = true launches the wavefront-specialised kernel (8 consumer + 3 service wavefronts).
 template <class Cfg, bool WS = false>
 int launch_grouped(const moe_bf16* A, const moe_bf16* B0, const moe_bf16* B1, moe_bf16* C,
-                   const int32_t* offsets, int R, int E, int N, int K, hipStream_t s) {
+                   const int32_t* offsets, const int32_t* row_index, int index_div, int R, int E,
+                   int N, int K, hipStream_t s) {
     if (N % Cfg::BN_OUT != 0 || K % Cfg::BK != 0) return MOE_ERR_UNSUPPORTED_SHAPE;
     using Kernel = void (*)(const uint16_t*, const uint16_t*, const uint16_t*, uint16_t*,
-                            const int32_t*, int, int, int);
+                            const int32_t*, const int32_t*, int, int, int, int);
     Kernel kern;
     if constexpr (WS) kern = gemm::grouped_gemm_ws_kernel<Cfg>;
     else kern = gemm::grouped_gemm_kernel<Cfg>;
@@ -40,7 +41,7 @@ int launch_grouped(const moe_bf16* A, const moe_bf16* B0, const moe_bf16* B1, mo
     grid = (grid + gemm::kXcds - 1) / gemm::kXcds * gemm::kXcds;
     if (grid > 0x7fffffffLL) return MOE_ERR_UNSUPPORTED_SHAPE;
     hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(grid)), dim3(kThreads), Cfg::SMEM, s,
-                       A, B0, B1, C, offsets, E, N, K);
+                       A, B0, B1, C, offsets, row_index, index_div, E, N, K);
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
 
@@ -71,13 +72,18 @@ using DownSmall   = Config<64, 64, 64, 1, 2, 4, false>;
 
 void set_gemm_config(int cfg) { g_forced_config = cfg; }
 
-int launch_gateup(const moe_bf16* x_perm, const int32_t* offsets, int R, int d, int f, int E,
-                  const moe_bf16* W1, const moe_bf16* W3, moe_bf16* H, hipStream_t s) {
+// `a` is the grouped activation matrix [R, d] when row_index is NULL; otherwise it is the
+// token matrix [T, d] and grouped row p reads token row_index[p] / index_div (the caller makes
+// sure that T * d * 2 bytes fit a 32-bit offset).
+int launch_gateup(const moe_bf16* a, const int32_t* row_index, int index_div,
+                  const int32_t* offsets, int R, int d, int f, int E, const moe_bf16* W1,
+                  const moe_bf16* W3, moe_bf16* H, hipStream_t s) {
     if (R == 0) return MOE_OK;
+    const moe_bf16* x_perm = a;
     switch (pick_config(R, E)) {
-        case 0: return launch_grouped<GateUpLarge, true>(x_perm, W1, W3, H, offsets, R, E, f, d, s);
-        case 1: return launch_grouped<GateUpMid>(x_perm, W1, W3, H, offsets, R, E, f, d, s);
-        default: return launch_grouped<GateUpSmall>(x_perm, W1, W3, H, offsets, R, E, f, d, s);
+        case 0: return launch_grouped<GateUpLarge, true>(x_perm, W1, W3, H, offsets, row_index, index_div, R, E, f, d, s);
+        case 1: return launch_grouped<GateUpMid>(x_perm, W1, W3, H, offsets, row_index, index_div, R, E, f, d, s);
+        default: return launch_grouped<GateUpSmall>(x_perm, W1, W3, H, offsets, row_index, index_div, R, E, f, d, s);
     }
 }
 
@@ -85,14 +91,14 @@ int launch_down(const moe_bf16* H, const int32_t* offsets, int R, int d, int f, 
                 const moe_bf16* W2, moe_bf16* y_perm, hipStream_t s) {
     if (R == 0) return MOE_OK;
     switch (pick_config(R, E)) {
-        case 0: return launch_grouped<DownLarge, true>(H, W2, nullptr, y_perm, offsets, R, E, d, f, s);
+        case 0: return launch_grouped<DownLarge, true>(H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
         case 1:
             // HBM-bound: wide tiles stream more bytes per workgroup, but only if there are
             // enough of them to occupy the 256 compute units (about one m-tile per expert).
             if (static_cast<long long>(E) * (d / 256) >= 160 && d % 256 == 0)
-                return launch_grouped<DownMidWide>(H, W2, nullptr, y_perm, offsets, R, E, d, f, s);
-            return launch_grouped<DownMid>(H, W2, nullptr, y_perm, offsets, R, E, d, f, s);
-        default: return launch_grouped<DownSmall>(H, W2, nullptr, y_perm, offsets, R, E, d, f, s);
+                return launch_grouped<DownMidWide>(H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
+            return launch_grouped<DownMid>(H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
+        default: return launch_grouped<DownSmall>(H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
     }
 }
 

@@ -235,12 +235,28 @@ __device__ __forceinline__ const uint16_t* weight_row_ptr(const TileCoord& tc, i
     return base + (static_cast<size_t>(tc.expert) * N + col0) * K;
 }
 
+// Row of A, relative to a_origin(), that feeds row r of the tile. Without an index the A
+// matrix is already grouped: the origin is the tile's first row and the answer is r. With one,
+// A holds one row per token, the origin is A itself and grouped row p reads the token
+// row_index[p] / index_div (the permutation's flat id t*k+s divided by k) — the row gather
+// fused into the operand load. Offsets from the origin are 32-bit: the caller guarantees
+// that the token matrix is smaller than 4 GiB when it passes an index.
+__device__ __forceinline__ int source_row(const TileCoord& tc, int r,
+                                          const int32_t* __restrict__ row_index, int index_div) {
+    return row_index ? row_index[tc.row0 + r] / index_div : r;
+}
+__device__ __forceinline__ const uint16_t* a_origin(const uint16_t* A, const TileCoord& tc,
+                                                    const int32_t* row_index, int K) {
+    return row_index ? A : A + static_cast<size_t>(tc.row0) * K;
+}
+
 // ---- kernel 1: every wavefront loads and computes ------------------------------------------
 template <class Cfg>
 __global__ __launch_bounds__(Cfg::NTHREADS) void grouped_gemm_kernel(
     const uint16_t* __restrict__ A, const uint16_t* __restrict__ B0,
     const uint16_t* __restrict__ B1, uint16_t* __restrict__ C,
-    const int32_t* __restrict__ offsets, int E, int N, int K) {
+    const int32_t* __restrict__ offsets, const int32_t* __restrict__ row_index, int index_div,
+    int E, int N, int K) {
     constexpr int BM = Cfg::BM, BK = Cfg::BK, WN = Cfg::WN, NW = Cfg::NW;
     constexpr int TM = Cfg::TM, TN = Cfg::TN;
     constexpr int CPR = Cfg::CPR, RPI = Cfg::RPI, NIA = Cfg::NIA, NIB = Cfg::NIB;
@@ -262,14 +278,14 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void grouped_gemm_kernel(
     //      must fetch logical chunk (l%CPR) ^ swz(row). A rows past the group's end are
     //      clamped to its last row (always in bounds; masked at the store).
     const int lrow = lane / CPR, lpos = lane % CPR;
-    const uint16_t* a_base = A + static_cast<size_t>(tc.row0) * K;   // wave-uniform
+    const uint16_t* a_base = a_origin(A, tc, row_index, K);
     uint32_t a_voff[LA], a_lds[LA];
 #pragma unroll
     for (int i = 0; i < LA; ++i) {
         const int q = wave * LA + i;
         const int r = q * RPI + lrow;
-        const int rr = min(r, tc.rows - 1);
-        a_voff[i] = (static_cast<uint32_t>(rr) * K + ((lpos ^ swz<BK>(r)) * 8)) * 2u;
+        const int src = source_row(tc, min(r, tc.rows - 1), row_index, index_div);
+        a_voff[i] = (static_cast<uint32_t>(src) * K + ((lpos ^ swz<BK>(r)) * 8)) * 2u;
         a_lds[i] = q * 1024;
     }
     const uint16_t* b_base[LB];
@@ -334,7 +350,8 @@ template <class Cfg>
 __global__ __launch_bounds__(Cfg::NTHREADS + kWsExtraWaves * 64) void grouped_gemm_ws_kernel(
     const uint16_t* __restrict__ A, const uint16_t* __restrict__ B0,
     const uint16_t* __restrict__ B1, uint16_t* __restrict__ C,
-    const int32_t* __restrict__ offsets, int E, int N, int K) {
+    const int32_t* __restrict__ offsets, const int32_t* __restrict__ row_index, int index_div,
+    int E, int N, int K) {
     constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, WN = Cfg::WN, NW = Cfg::NW;
     constexpr int TM = Cfg::TM, TN = Cfg::TN;
     constexpr int CPR = Cfg::CPR, RPI = Cfg::RPI, NIA = Cfg::NIA, NIB = Cfg::NIB;
@@ -366,7 +383,8 @@ __global__ __launch_bounds__(Cfg::NTHREADS + kWsExtraWaves * 64) void grouped_ge
             const size_t ko = static_cast<size_t>(min(kt + kPrefetchDist, KT - 1)) * BK;
             for (int r = 0; r < a_rows; r += 64) {
                 const int row = min(min(a0 + r + lane, a0 + a_rows - 1), tc.rows - 1);
-                const uint16_t* p = A + static_cast<size_t>(tc.row0 + row) * K + ko;
+                const uint16_t* p = a_origin(A, tc, row_index, K) +
+                                    static_cast<size_t>(source_row(tc, row, row_index, index_div)) * K + ko;
                 asm volatile("global_load_dword %0, %1, off" : "+v"(sink) : "v"(p) : "memory");
             }
             for (int r = 0; r < b_rows; r += 64) {
@@ -394,10 +412,11 @@ __global__ __launch_bounds__(Cfg::NTHREADS + kWsExtraWaves * 64) void grouped_ge
 #pragma unroll
         for (int q = 0; q < NI; ++q) {
             const int r = q * RPI + lrow;
-            const int rr = is_b ? lrow : min(r, tc.rows - 1);
+            const int rr = is_b ? lrow
+                                : source_row(tc, min(r, tc.rows - 1), row_index, index_div);
             voff[q] = (static_cast<uint32_t>(rr) * K + ((lpos ^ swz<BK>(r)) * 8)) * 2u;
         }
-        const uint16_t* a_base = A + static_cast<size_t>(tc.row0) * K;
+        const uint16_t* a_base = a_origin(A, tc, row_index, K);
         auto issue = [&](int stage, int kt) {
             const uint32_t sbase = stage * Cfg::STAGE_BYTES + (is_b ? Cfg::A_BYTES : 0);
             const size_t koff = static_cast<size_t>(kt) * BK;

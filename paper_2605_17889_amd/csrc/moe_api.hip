@@ -107,11 +107,19 @@ int forward_chunk(moe_ctx* c, const moe_bf16* x, const float* w_router, const fl
                               c->scratch, s);
     });
     if (rc != MOE_OK) return rc;
-    rc = run_stage(c, MOE_STAGE_GATHER, 1, s,
-                   [&] { return launch_gather(x, c->perm, c->offsets, R, d, k, E, c->x_perm, s); });
-    if (rc != MOE_OK) return rc;
+    // The row gather x -> x_perm is fused into the gate/up kernel's operand loads (it reads
+    // token row perm[p] / k directly) whenever a token row's byte offset fits 32 bits.
+    const bool fuse_gather = static_cast<unsigned long long>(T) * d * 2ull < (1ull << 32);
+    if (!fuse_gather) {
+        rc = run_stage(c, MOE_STAGE_GATHER, 1, s, [&] {
+            return launch_gather(x, c->perm, c->offsets, R, d, k, E, c->x_perm, s);
+        });
+        if (rc != MOE_OK) return rc;
+    }
     rc = run_stage(c, MOE_STAGE_GATEUP, 1, s, [&] {
-        return launch_gateup(c->x_perm, c->offsets, R, d, f, E, W1, W3, c->H, s);
+        return fuse_gather
+                   ? launch_gateup(x, c->perm, k, c->offsets, R, d, f, E, W1, W3, c->H, s)
+                   : launch_gateup(c->x_perm, nullptr, 1, c->offsets, R, d, f, E, W1, W3, c->H, s);
     });
     if (rc != MOE_OK) return rc;
     rc = run_stage(c, MOE_STAGE_DOWN, 1, s, [&] {
@@ -234,7 +242,7 @@ int moe_expert_ffn(moe_ctx* c, const moe_bf16* x_perm, const int32_t* offsets, i
     if (!x_perm || !offsets || !W1 || !W3 || !W2 || !y_perm) return MOE_ERR_INVALID_ARG;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const moe_shape& sh = c->shape;
-    int rc = launch_gateup(x_perm, offsets, R, sh.d_model, sh.d_ff, sh.E, W1, W3, c->H, s);
+    int rc = launch_gateup(x_perm, nullptr, 1, offsets, R, sh.d_model, sh.d_ff, sh.E, W1, W3, c->H, s);
     if (rc != MOE_OK) return rc;
     return launch_down(c->H, offsets, R, sh.d_model, sh.d_ff, sh.E, W2, y_perm, s);
 }
