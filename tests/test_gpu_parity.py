@@ -449,3 +449,62 @@ def test_layer_mixtral8x22b_zipf(experts_8x22b, preset):
     want, _, _ = ref.layer_tokens(Hh["x"], Hh["w_router"], Hh["bias"], Hh["W1"], Hh["W3"], Hh["W2"], cfg.k, tokens)
     assert_close_ffn(bits(y)[tokens], want, f"{preset} ({tokens.size} tokens)")
     ctx.close()
+
+
+# ------------------------------------------------------- other expert counts and top-k values
+@pytest.mark.parametrize("T,d,f,E,k,use_bias", [
+    (300, 512, 256, 64, 8, True),      # many small experts, some of them empty
+    (257, 1024, 512, 16, 4, False),
+    (40, 512, 256, 3, 3, True),        # k = E: every token visits every expert
+    (129, 512, 768, 5, 1, False),      # top-1
+])
+def test_layer_other_expert_shapes(T, d, f, E, k, use_bias):
+    say(f"layer T={T} d={d} f={f} E={E} k={k}")
+    cfg = synth.LayerConfig("custom", T, d, f, E, k, seed=900 + E)
+    L = synth.make_layer(cfg, "cuda")
+    if use_bias:
+        g = torch.Generator(device="cpu").manual_seed(E)
+        L["bias"] = (torch.randn(E, generator=g) * 1.5).cuda()
+    Hh = host_layer(L)
+    y, ctx = run_layer(cfg, L)
+    routing = fetch_routing(ctx, T)
+    check_routing_exact(cfg, Hh, routing, T)
+    want, _, _ = ref.layer_tokens(Hh["x"], Hh["w_router"], Hh["bias"], Hh["W1"], Hh["W3"], Hh["W2"], k)
+    assert_close_ffn(bits(y), want, f"E={E} k={k}")
+    ym, _ = run_layer(cfg, L, micro=37, ctx=ctx)
+    assert torch.equal(ym.view(torch.int16), y.view(torch.int16)), "micro-batched output differs"
+    ctx.close()
+
+
+def test_permute_drops_out_of_range_experts():
+    """An expert index outside [0, E) is dropped from every group: inv_perm = -1, counts and
+    offsets only cover the valid ids, and the remaining ids keep their stable order."""
+    T, E, k, d = 50, 4, 2, 512
+    rng = np.random.default_rng(77)
+    idx = rng.integers(0, E, size=(T, k)).astype(np.int32)
+    bad = [(3, 0), (17, 1), (49, 0)]
+    for t, s in bad:
+        idx[t, s] = E + 5 if (t + s) % 2 else -1
+    flat = idx.reshape(-1)
+    valid = (flat >= 0) & (flat < E)
+    ids = np.nonzero(valid)[0]
+    order = ids[np.argsort(flat[ids], kind="stable")]
+    ctx = B.MoeContext(T, d, 256, E, k)
+    R = T * k
+    counts = torch.empty(E, dtype=torch.int32, device="cuda")
+    offsets = torch.empty(E + 1, dtype=torch.int32, device="cuda")
+    perm = torch.full((R,), -7, dtype=torch.int32, device="cuda")
+    inv = torch.empty(R, dtype=torch.int32, device="cuda")
+    x = torch.ones((T, d), dtype=torch.bfloat16, device="cuda")
+    xp = torch.full((R, d), 3.0, dtype=torch.bfloat16, device="cuda")
+    B.moe_permute(ctx, dev(idx), T, counts, offsets, perm, inv, x, xp)
+    torch.cuda.synchronize()
+    assert np.array_equal(counts.cpu().numpy(), np.bincount(flat[valid], minlength=E))
+    assert int(offsets.cpu().numpy()[-1]) == len(ids)
+    assert np.array_equal(perm.cpu().numpy()[:len(ids)], order)
+    inv_h = inv.cpu().numpy()
+    assert np.all(inv_h[~valid] == -1)
+    assert np.array_equal(inv_h[order], np.arange(len(ids)))
+    xp_h = xp.float().cpu().numpy()
+    assert np.all(xp_h[:len(ids)] == 1.0) and np.all(xp_h[len(ids):] == 0.0)
+    ctx.close()
