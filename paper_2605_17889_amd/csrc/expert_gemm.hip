@@ -17,22 +17,31 @@ namespace {
 
 using gemm::Config;
 
-// WS = true launches the wavefront-specialised kernel (8 consumer + 3 service wavefronts).
-template <class Cfg, bool WS = false>
+// NA, NB > 0 launch the pipelined kernel with operand rings of NA and NB stages; otherwise the
+// generic kernel with Cfg::NSTAGE stages.
+template <class Cfg, int NA = 0, int NB = 0>
 int launch_grouped(const moe_bf16* A, const moe_bf16* B0, const moe_bf16* B1, moe_bf16* C,
                    const int32_t* offsets, const int32_t* row_index, int index_div, int R, int E,
                    int N, int K, hipStream_t s) {
+    constexpr bool RING = NA > 0;
     if (N % Cfg::BN_OUT != 0 || K % Cfg::BK != 0) return MOE_ERR_UNSUPPORTED_SHAPE;
+    if (RING && K / Cfg::BK < (NA > NB ? NA : NB)) return MOE_ERR_UNSUPPORTED_SHAPE;
     using Kernel = void (*)(const uint16_t*, const uint16_t*, const uint16_t*, uint16_t*,
                             const int32_t*, const int32_t*, int, int, int, int);
     Kernel kern;
-    if constexpr (WS) kern = gemm::grouped_gemm_ws_kernel<Cfg>;
-    else kern = gemm::grouped_gemm_kernel<Cfg>;
-    constexpr int kThreads = Cfg::NTHREADS + (WS ? gemm::kWsExtraWaves * 64 : 0);
+    int smem;
+    if constexpr (RING) {
+        kern = gemm::grouped_gemm_ring_kernel<Cfg, NA, NB>;
+        smem = gemm::RingCfg<Cfg, NA, NB>::SMEM;
+    } else {
+        kern = gemm::grouped_gemm_kernel<Cfg>;
+        smem = Cfg::SMEM;
+    }
+    constexpr int kThreads = Cfg::NTHREADS;
     static bool attr_set = false;
     if (!attr_set) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::SMEM) != hipSuccess)
+                                hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
             return MOE_ERR_HIP;
         attr_set = true;
     }
@@ -40,7 +49,7 @@ int launch_grouped(const moe_bf16* A, const moe_bf16* B0, const moe_bf16* B1, mo
     long long grid = max_mt * (N / Cfg::BN_OUT);
     grid = (grid + gemm::kXcds - 1) / gemm::kXcds * gemm::kXcds;
     if (grid > 0x7fffffffLL) return MOE_ERR_UNSUPPORTED_SHAPE;
-    hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(grid)), dim3(kThreads), Cfg::SMEM, s,
+    hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(grid)), dim3(kThreads), smem, s,
                        A, B0, B1, C, offsets, row_index, index_div, E, N, K);
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
@@ -50,7 +59,7 @@ int g_forced_config = -1;   // -1: automatic; 0,1,2: force (tests / tuning)
 
 int pick_config(int R, int E) {
     if (g_forced_config >= 0) return g_forced_config;
-    // 0: compute-bound groups (wavefront-specialised 256x256 tiles). 1: groups of up to ~128
+    // 0: compute-bound groups (pipelined 256x256 tiles). 1: groups of up to ~128
     // rows: the kernel streams the weights once per 128-row m-tile and is HBM-bound. 2: a few
     // rows per expert (64-row tiles).
     const int avg = R / (E > 0 ? E : 1);
@@ -81,7 +90,7 @@ int launch_gateup(const moe_bf16* a, const int32_t* row_index, int index_div,
     if (R == 0) return MOE_OK;
     const moe_bf16* x_perm = a;
     switch (pick_config(R, E)) {
-        case 0: return launch_grouped<GateUpLarge, true>(x_perm, W1, W3, H, offsets, row_index, index_div, R, E, f, d, s);
+        case 0: return launch_grouped<GateUpLarge, 2, 3>(x_perm, W1, W3, H, offsets, row_index, index_div, R, E, f, d, s);
         case 1: return launch_grouped<GateUpMid>(x_perm, W1, W3, H, offsets, row_index, index_div, R, E, f, d, s);
         default: return launch_grouped<GateUpSmall>(x_perm, W1, W3, H, offsets, row_index, index_div, R, E, f, d, s);
     }
@@ -91,7 +100,7 @@ int launch_down(const moe_bf16* H, const int32_t* offsets, int R, int d, int f, 
                 const moe_bf16* W2, moe_bf16* y_perm, hipStream_t s) {
     if (R == 0) return MOE_OK;
     switch (pick_config(R, E)) {
-        case 0: return launch_grouped<DownLarge, true>(H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
+        case 0: return launch_grouped<DownLarge, 2, 3>(H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
         case 1:
             // HBM-bound: wide tiles stream more bytes per workgroup, but only if there are
             // enough of them to occupy the 256 compute units (about one m-tile per expert).

@@ -1,33 +1,38 @@
-// Grouped expert GEMM kernel for gfx950 (device code; included by expert_gemm.hip).
+// Grouped expert GEMM kernels for gfx950 (device code; included by expert_gemm.hip).
 //
 //   C[p, n] = sum_k A[p, k] * B_e[n, k]           for the rows p of expert e's group,
 // both operands contiguous along k ("NT"), bf16 in, fp32 accumulation on
-// v_mfma_f32_32x32x16_bf16, bf16 out. With DUAL, a tile carries BN/2 rows of W1 and the
+// v_mfma_f32_16x16x32_bf16, bf16 out. With DUAL, a tile carries BN/2 rows of W1 and the
 // matching BN/2 rows of W3 (interleaved in blocks of 32) and stores SiLU(gate)*up.
 //
-// Data path: global memory -> LDS by direct-to-LDS loads (no VGPR staging), a ring of LDS
-// stages, one workgroup barrier per k-step; LDS -> VGPR by 16-byte reads of a swizzled
-// layout; MFMA. Tiles are enumerated on the device from `offsets`.
+// Data path: global memory -> LDS by direct-to-LDS loads (no VGPR staging); LDS -> VGPR by
+// 16-byte reads of a swizzled layout; MFMA. Tiles are enumerated on the device from `offsets`.
 //
-// Two kernels share the tile mapping, the LDS layout, the MFMA loop and the epilogue:
-//   grouped_gemm_kernel     every wavefront loads its share of a stage and then computes
-//                           (small tiles: decode and micro-batch sized expert groups);
-//   grouped_gemm_ws_kernel  wavefront-specialised: 8 consumer wavefronts only read LDS and
-//                           issue MFMAs, 2 producer wavefronts only issue the direct-to-LDS
-//                           loads (the texture-address unit accepts one 1 KB wavefront load
-//                           per ~25 cycles, which would otherwise stall the MFMA issue of the
-//                           wavefront that waits for it), and 1 wavefront touches the lines of
-//                           a later k-step so that the loads find them in L2.
+// The 16x16x32 instruction is used instead of 32x32x16 because it does the same work per cycle
+// with half the accumulator updates per multiply-add: under the board's power limit a loop of
+// it sustains ~13 % more FLOP/s on random operands. The weight fragment is the first MFMA
+// operand, so a lane ends up with four consecutive output columns of one row (one 8-byte store).
+//
+// Two kernels share the tile mapping, the LDS layout, the fragment plan and the epilogue:
+//   grouped_gemm_kernel       ring of NSTAGE LDS stages, compiler-scheduled k-step (small tiles:
+//                           decode and micro-batch sized expert groups, HBM-bound);
+//   grouped_gemm_ring_kernel  hand-placed software pipeline for the large compute-bound tiles:
+//                           the fragments of the next half k-step are read from LDS while the
+//                           MFMAs of the current one issue, the workgroup barrier sits in the
+//                           middle of a k-step so that MFMAs are ready on both sides of it, the
+//                           direct-to-LDS loads are spread between the MFMAs, and the two
+//                           operands have LDS rings of different depth.
 #pragma once
+#include <type_traits>
+
 #include "common.h"
 
 namespace moe {
 namespace gemm {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef float f32x2 __attribute__((ext_vector_type(2)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kXcds = 8;     // workgroups are dealt round-robin to the 8 XCDs (own L2 each)
 constexpr int kGroupM = 8;   // m-tiles that sweep the n-tiles together (share weight tiles)
@@ -83,8 +88,8 @@ __device__ __forceinline__ TileCoord locate_tile(const int32_t* __restrict__ off
 
 // LDS tile layout: rows of BK bf16 in 16-byte chunks; logical chunk c of row r is stored at
 // chunk position c ^ swz(r). LDS has 64 four-byte banks and a 16-byte read is served 16 lanes
-// at a time, so the swizzle makes any 16 consecutive rows at one logical chunk hit 16 distinct
-// 16-byte slots of a 256-byte bank window.
+// at a time; the 16 lanes of a fragment read the same logical chunk of 16 consecutive rows,
+// which the swizzle spreads over 16 distinct 16-byte slots of a 256-byte bank window.
 template <int BK>
 __device__ __forceinline__ int swz(int row) {
     if (BK == 64) return (row >> 1) & 7;     // 128-byte rows: 2 rows per bank window
@@ -93,8 +98,8 @@ __device__ __forceinline__ int swz(int row) {
 
 // One direct-to-LDS load: every lane fetches 16 bytes from sbase + voff and the wavefront's
 // 64 x 16 bytes land contiguously at LDS byte offset lds_off (wave-uniform, passed in M0).
-// The compiler is not told that this is a memory operation with a counter: the kernel places
-// its own s_waitcnt vmcnt(n) before the barrier that publishes a stage.
+// The compiler is not told that this is a memory operation with a counter: the kernels place
+// their own s_waitcnt vmcnt(n) before the barrier that publishes a stage.
 __device__ __forceinline__ void dma16(const void* sbase, uint32_t voff, uint32_t lds_off) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :: "s"(lds_off), "v"(voff), "s"(sbase) : "memory", "m0");
@@ -107,111 +112,120 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
 
 __device__ __forceinline__ float silu(float a) { return a / (1.0f + __expf(-a)); }
 
-__device__ __forceinline__ uint16_t to_bf16(float v) {
-    __bf16 h = static_cast<__bf16>(v);       // v_cvt_pk_bf16_f32: round to nearest even
-    return *reinterpret_cast<uint16_t*>(&h);
-}
-
 template <int BM_, int BN_, int BK_, int WM_, int WN_, int NSTAGE_, bool DUAL_>
 struct Config {
     static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_, NSTAGE = NSTAGE_;
     static constexpr bool DUAL = DUAL_;
     static constexpr int NW = WM * WN, NTHREADS = NW * 64;
-    static constexpr int WTM = BM / WM, WTN = BN / WN, TM = WTM / 32, TN = WTN / 32;
+    static constexpr int WTM = BM / WM, WTN = BN / WN, TM = WTM / 16, TN = WTN / 16;
+    static constexpr int KSUB = BK / 32;                   // MFMA k-substeps per stage
+    static constexpr int ROW_BYTES = BK * 2;
     static constexpr int CPR = BK / 8;                     // 16-byte chunks per row
     static constexpr int RPI = 64 / CPR;                   // rows one wavefront load covers
-    static constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
+    static constexpr int TILE_STEP = 16 * ROW_BYTES;       // LDS bytes between 16-row tiles
+    static constexpr int A_BYTES = BM * ROW_BYTES, B_BYTES = BN * ROW_BYTES;
     static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
     static constexpr int SMEM = NSTAGE * STAGE_BYTES;
     static constexpr int NIA = BM / RPI, NIB = BN / RPI;   // wavefront loads per stage
     static constexpr int LPW = (NIA + NIB) / NW;           // ... per wavefront
     static constexpr int BN_OUT = DUAL ? BN / 2 : BN;      // output columns per tile
-    static_assert(BK == 64 || BK == 32, "BK");
-    static_assert(BM % (WM * 32) == 0 && BN % (WN * 32) == 0, "wave tile");
-    static_assert(!DUAL || TN % 2 == 0, "gate/up pairs must live in one wave");
+    static_assert(BK == 64 || BK == 32, "LDS rows of 128 or 64 bytes");
+    static_assert(BM % (WM * 16) == 0 && BN % (WN * 16) == 0, "wave tile");
+    static_assert(!DUAL || WTN % 64 == 0, "gate/up blocks of 32+32 rows must live in one wave");
     static_assert(NIA % NW == 0 && NIB % NW == 0, "loads must split evenly over wavefronts");
     static_assert(NSTAGE >= 2 && SMEM <= 160 * 1024, "LDS budget");
 };
 
-// ---- pieces shared by both kernels -------------------------------------------------------
+// ---- pieces shared by the kernels ---------------------------------------------------------
 
-// Per-lane LDS byte offsets (inside a stage) of the MFMA operand fragments of k-substep 0 and
-// the swizzle term that the other substeps xor in.
+// MFMA 16x16x32 operand fragment: lane l supplies 8 consecutive k (k-group l >> 4) of operand
+// row l & 15. Per-lane LDS byte offsets inside a stage of the fragment of this wavefront's
+// first A / B tile at each k-substep; tile i of the wave is 16 rows (TILE_STEP bytes) further on
+// (the swizzle only depends on row & 15, so it is the same for every tile).
 template <class Cfg>
 struct FragPlan {
-    int a_off[Cfg::TM], a_sw[Cfg::TM], b_off[Cfg::TN], b_sw[Cfg::TN];
-    int frag_row, frag_half;
+    uint32_t a_off[Cfg::KSUB], b_off[Cfg::KSUB];
+    int frag_row, frag_kg;
     __device__ __forceinline__ void init(int lane, int wm, int wn) {
-        frag_row = lane & 31;      // operand row inside a 32-row MFMA tile
-        frag_half = lane >> 5;     // which 8 of the 16 k this lane feeds
+        frag_row = lane & 15;
+        frag_kg = lane >> 4;
 #pragma unroll
-        for (int i = 0; i < Cfg::TM; ++i) {
-            const int r = wm * Cfg::WTM + i * 32 + frag_row;
-            a_off[i] = r * (Cfg::BK * 2);
-            a_sw[i] = swz<Cfg::BK>(r);
-        }
-#pragma unroll
-        for (int j = 0; j < Cfg::TN; ++j) {
-            const int r = wn * Cfg::WTN + j * 32 + frag_row;
-            b_off[j] = Cfg::A_BYTES + r * (Cfg::BK * 2);
-            b_sw[j] = swz<Cfg::BK>(r);
+        for (int kk = 0; kk < Cfg::KSUB; ++kk) {
+            const uint32_t chunk =
+                static_cast<uint32_t>(((kk * 4 + frag_kg) ^ swz<Cfg::BK>(frag_row)) << 4);
+            a_off[kk] = (wm * Cfg::WTM + frag_row) * Cfg::ROW_BYTES + chunk;
+            b_off[kk] = Cfg::A_BYTES + (wn * Cfg::WTN + frag_row) * Cfg::ROW_BYTES + chunk;
         }
     }
 };
 
+__device__ __forceinline__ bf16x8 lds16(const unsigned char* p) {
+    return *reinterpret_cast<const bf16x8*>(p);
+}
+
+// acc (16x16, transposed: rows = weight rows, columns = activation rows) += W_frag * X_frag
+__device__ __forceinline__ f32x4 mma16(const bf16x8& w, const bf16x8& x, const f32x4& acc) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(w, x, acc, 0, 0, 0);
+}
+
+// The same instruction with the accumulator pinned to the accumulation registers (AGPRs). The
+// pipelined kernel uses it so that its 128 or 256 accumulator registers never compete with the
+// fragment registers (left to itself the register allocator shuffles accumulators between the
+// two register classes inside the k-loop). The compiler does not know that this is an MFMA:
+// it still waits for the LDS reads that feed it, but the kernel must pad by hand before
+// anything other than an MFMA touches the accumulators (see mfma_drain()).
+__device__ __forceinline__ void mma16_agpr(const bf16x8& w, const bf16x8& x, f32x4& acc) {
+    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(w), "v"(x));
+}
+// Wait states between the last MFMA and the first ordinary read of its result.
+__device__ __forceinline__ void mfma_drain() {
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+}
+
 // All k-substeps of one stage: acc[i][j] += A_i * B_j, k ascending.
 template <class Cfg>
 __device__ __forceinline__ void mma_stage(const unsigned char* s, const FragPlan<Cfg>& fp,
-                                          f32x16 (&acc)[Cfg::TM][Cfg::TN]) {
+                                          f32x4 (&acc)[Cfg::TM][Cfg::TN]) {
 #pragma unroll
-    for (int kk = 0; kk < Cfg::BK / 16; ++kk) {
+    for (int kk = 0; kk < Cfg::KSUB; ++kk) {
         bf16x8 af[Cfg::TM], bfr[Cfg::TN];
-        const int c = kk * 2 + fp.frag_half;
 #pragma unroll
-        for (int i = 0; i < Cfg::TM; ++i)
-            af[i] = *reinterpret_cast<const bf16x8*>(s + fp.a_off[i] + ((c ^ fp.a_sw[i]) << 4));
+        for (int i = 0; i < Cfg::TM; ++i) af[i] = lds16(s + fp.a_off[kk] + i * Cfg::TILE_STEP);
 #pragma unroll
-        for (int j = 0; j < Cfg::TN; ++j)
-            bfr[j] = *reinterpret_cast<const bf16x8*>(s + fp.b_off[j] + ((c ^ fp.b_sw[j]) << 4));
+        for (int j = 0; j < Cfg::TN; ++j) bfr[j] = lds16(s + fp.b_off[kk] + j * Cfg::TILE_STEP);
 #pragma unroll
         for (int i = 0; i < Cfg::TM; ++i)
 #pragma unroll
-            for (int j = 0; j < Cfg::TN; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+            for (int j = 0; j < Cfg::TN; ++j) acc[i][j] = mma16(bfr[j], af[i], acc[i][j]);
     }
 }
 
-// Epilogue. MFMA 32x32 result layout: lane holds column (lane & 31); register 4*q + r is row
-// 8*q + 4*(lane >> 5) + r. With DUAL, accumulator tiles 2j / 2j+1 are gate / up of the same
-// output columns and SiLU(gate)*up is applied in registers.
+// Epilogue. Result layout of the transposed 16x16 tile: lane holds activation row (lane & 15)
+// and the four output columns 4 * (lane >> 4) + r in registers r = 0..3. With DUAL, B-tile rows
+// come in blocks of 32 W1 rows followed by the 32 W3 rows of the same output columns, so
+// accumulator tiles j and j + 2 (j & 2 == 0) are gate and up of the same columns.
 template <class Cfg>
-__device__ __forceinline__ void store_tile(const f32x16 (&acc)[Cfg::TM][Cfg::TN], const TileCoord& tc,
+__device__ __forceinline__ void store_tile(const f32x4 (&acc)[Cfg::TM][Cfg::TN], const TileCoord& tc,
                                            const FragPlan<Cfg>& fp, int wm, int wn,
                                            uint16_t* __restrict__ C, int ldc) {
     constexpr bool DUAL = Cfg::DUAL;
 #pragma unroll
     for (int i = 0; i < Cfg::TM; ++i) {
+        const int row = wm * Cfg::WTM + i * 16 + fp.frag_row;
+        if (row >= tc.rows) continue;
+        uint16_t* crow = C + static_cast<size_t>(tc.row0 + row) * ldc + tc.nt * Cfg::BN_OUT + 4 * fp.frag_kg;
 #pragma unroll
-        for (int j = 0; j < Cfg::TN; j += (DUAL ? 2 : 1)) {
-            int col;
-            if (DUAL) {
-                const int b32 = (wn * Cfg::WTN) / 32 + j;
-                col = tc.nt * Cfg::BN_OUT + (b32 >> 1) * 32 + fp.frag_row;
-            } else {
-                col = tc.nt * Cfg::BN_OUT + wn * Cfg::WTN + j * 32 + fp.frag_row;
+        for (int j = 0; j < Cfg::TN; ++j) {
+            if (DUAL && (j & 2)) continue;
+            const int r0 = wn * Cfg::WTN + j * 16;                 // first B-tile row of tile j
+            const int col = DUAL ? (r0 >> 6) * 32 + (r0 & 31) : r0;
+            bf16x4 o;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float v = DUAL ? silu(acc[i][j][r]) * acc[i][DUAL ? j + 2 : j][r] : acc[i][j][r];
+                o[r] = static_cast<__bf16>(v);                     // round to nearest even
             }
-#pragma unroll
-            for (int q = 0; q < 4; ++q)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int row = wm * Cfg::WTM + i * 32 + 8 * q + 4 * fp.frag_half + r;
-                    if (row < tc.rows) {
-                        float v;
-                        if (DUAL) v = silu(acc[i][j][4 * q + r]) * acc[i][j + (DUAL ? 1 : 0)][4 * q + r];
-                        else v = acc[i][j][4 * q + r];
-                        C[static_cast<size_t>(tc.row0 + row) * ldc + col] = to_bf16(v);
-                    }
-                }
+            *reinterpret_cast<bf16x4*>(crow + col) = o;
         }
     }
 }
@@ -250,18 +264,65 @@ __device__ __forceinline__ const uint16_t* a_origin(const uint16_t* A, const Til
     return row_index ? A : A + static_cast<size_t>(tc.row0) * K;
 }
 
-// ---- kernel 1: every wavefront loads and computes ------------------------------------------
+// Direct-to-LDS load plan of one wavefront. Wavefront load q of a stage covers tile rows
+// [q*RPI, (q+1)*RPI); lane l lands at row q*RPI + l/CPR, chunk position l%CPR, so it must
+// fetch logical chunk (l%CPR) ^ swz(row). A rows past the group's end are clamped to its last
+// row (always in bounds; masked at the store).
+template <class Cfg>
+struct LoadPlan {
+    static constexpr int LA = Cfg::NIA / Cfg::NW, LB = Cfg::NIB / Cfg::NW;
+    const uint16_t* a_base;
+    const uint16_t* b_base[LB];
+    uint32_t a_voff[LA], a_lds[LA], b_voff[LB], b_lds[LB];
+    __device__ __forceinline__ void init(const TileCoord& tc, int wave, int lane, const uint16_t* A,
+                                         const uint16_t* B0, const uint16_t* B1,
+                                         const int32_t* row_index, int index_div, int N, int K) {
+        const int lrow = lane / Cfg::CPR, lpos = lane % Cfg::CPR;
+        a_base = a_origin(A, tc, row_index, K);
+#pragma unroll
+        for (int i = 0; i < LA; ++i) {
+            const int q = wave * LA + i;
+            const int r = q * Cfg::RPI + lrow;
+            const int src = source_row(tc, min(r, tc.rows - 1), row_index, index_div);
+            a_voff[i] = (static_cast<uint32_t>(src) * K + ((lpos ^ swz<Cfg::BK>(r)) * 8)) * 2u;
+            a_lds[i] = q * 1024;
+        }
+#pragma unroll
+        for (int i = 0; i < LB; ++i) {
+            const int q = wave * LB + i;
+            const int r = q * Cfg::RPI + lrow;
+            b_base[i] = weight_row_ptr<Cfg>(tc, q * Cfg::RPI, B0, B1, N, K);
+            b_voff[i] = (static_cast<uint32_t>(lrow) * K + ((lpos ^ swz<Cfg::BK>(r)) * 8)) * 2u;
+            b_lds[i] = Cfg::A_BYTES + q * 1024;
+        }
+    }
+    // load number n (0 <= n < LA + LB) of k-step kt into the stage at LDS byte offset sbase
+    __device__ __forceinline__ void issue_one(int n, uint32_t sbase, size_t koff) const {
+        if (n < LA) dma16(a_base + koff, a_voff[n], sbase + a_lds[n]);
+        else dma16(b_base[n - LA] + koff, b_voff[n - LA], sbase + b_lds[n - LA]);
+    }
+    // single loads with explicit LDS region bases (operand rings of different depth)
+    __device__ __forceinline__ void issue_a(int i, uint32_t region, size_t koff) const {
+        dma16(a_base + koff, a_voff[i], region + a_lds[i]);
+    }
+    __device__ __forceinline__ void issue_b(int i, uint32_t region, size_t koff) const {
+        dma16(b_base[i] + koff, b_voff[i], region + (b_lds[i] - Cfg::A_BYTES));
+    }
+    __device__ __forceinline__ void issue_all(uint32_t sbase, size_t koff) const {
+#pragma unroll
+        for (int n = 0; n < LA + LB; ++n) issue_one(n, sbase, koff);
+    }
+};
+
+// ---- kernel 1: ring of stages, every wavefront loads and computes ---------------------------
 template <class Cfg>
 __global__ __launch_bounds__(Cfg::NTHREADS) void grouped_gemm_kernel(
     const uint16_t* __restrict__ A, const uint16_t* __restrict__ B0,
     const uint16_t* __restrict__ B1, uint16_t* __restrict__ C,
     const int32_t* __restrict__ offsets, const int32_t* __restrict__ row_index, int index_div,
     int E, int N, int K) {
-    constexpr int BM = Cfg::BM, BK = Cfg::BK, WN = Cfg::WN, NW = Cfg::NW;
-    constexpr int TM = Cfg::TM, TN = Cfg::TN;
-    constexpr int CPR = Cfg::CPR, RPI = Cfg::RPI, NIA = Cfg::NIA, NIB = Cfg::NIB;
-    constexpr int LA = NIA / NW, LB = NIB / NW, LPW = Cfg::LPW, NSTAGE = Cfg::NSTAGE;
-    static_assert(NIA % NW == 0 && NIB % NW == 0, "loads must split evenly over wavefronts");
+    constexpr int BM = Cfg::BM, BK = Cfg::BK, WN = Cfg::WN;
+    constexpr int TM = Cfg::TM, TN = Cfg::TN, LPW = Cfg::LPW, NSTAGE = Cfg::NSTAGE;
 
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
@@ -273,47 +334,14 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void grouped_gemm_kernel(
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WN, wn = wave % WN;
 
-    // ---- direct-to-LDS load plan. Wavefront load q of a stage covers tile rows
-    //      [q*RPI, (q+1)*RPI); lane l lands at row q*RPI + l/CPR, chunk position l%CPR, so it
-    //      must fetch logical chunk (l%CPR) ^ swz(row). A rows past the group's end are
-    //      clamped to its last row (always in bounds; masked at the store).
-    const int lrow = lane / CPR, lpos = lane % CPR;
-    const uint16_t* a_base = a_origin(A, tc, row_index, K);
-    uint32_t a_voff[LA], a_lds[LA];
-#pragma unroll
-    for (int i = 0; i < LA; ++i) {
-        const int q = wave * LA + i;
-        const int r = q * RPI + lrow;
-        const int src = source_row(tc, min(r, tc.rows - 1), row_index, index_div);
-        a_voff[i] = (static_cast<uint32_t>(src) * K + ((lpos ^ swz<BK>(r)) * 8)) * 2u;
-        a_lds[i] = q * 1024;
-    }
-    const uint16_t* b_base[LB];
-    uint32_t b_voff[LB], b_lds[LB];
-#pragma unroll
-    for (int i = 0; i < LB; ++i) {
-        const int q = wave * LB + i;
-        const int r = q * RPI + lrow;
-        b_base[i] = weight_row_ptr<Cfg>(tc, q * RPI, B0, B1, N, K);
-        b_voff[i] = (static_cast<uint32_t>(lrow) * K + ((lpos ^ swz<BK>(r)) * 8)) * 2u;
-        b_lds[i] = Cfg::A_BYTES + q * 1024;
-    }
-    auto issue = [&](int stage, int kt) {
-        const uint32_t sbase = stage * Cfg::STAGE_BYTES;
-        const size_t koff = static_cast<size_t>(kt) * BK;
-#pragma unroll
-        for (int i = 0; i < LA; ++i) dma16(a_base + koff, a_voff[i], sbase + a_lds[i]);
-#pragma unroll
-        for (int i = 0; i < LB; ++i) dma16(b_base[i] + koff, b_voff[i], sbase + b_lds[i]);
-    };
+    LoadPlan<Cfg> lp;
+    lp.init(tc, wave, lane, A, B0, B1, row_index, index_div, N, K);
 
-    f32x16 acc[TM][TN];
+    f32x4 acc[TM][TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.f;
+        for (int j = 0; j < TN; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
     FragPlan<Cfg> fp;
     fp.init(lane, wm, wn);
 
@@ -321,7 +349,7 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void grouped_gemm_kernel(
     const int KT = K / BK;
 #pragma unroll
     for (int s = 0; s < NSTAGE - 1; ++s)
-        if (s < KT) issue(s, s);
+        if (s < KT) lp.issue_all(s * Cfg::STAGE_BYTES, static_cast<size_t>(s) * BK);
     int stage = 0;
     for (int kt = 0; kt < KT; ++kt) {
         // The loads of k-step kt are the oldest in flight; up to NSTAGE-2 newer steps may stay
@@ -330,33 +358,110 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void grouped_gemm_kernel(
         __builtin_amdgcn_s_barrier();          // stage `stage` is complete for every wavefront
                                                // and stage (stage-1) is no longer being read
         const int nk = kt + NSTAGE - 1;
-        if (nk < KT) issue(stage == 0 ? NSTAGE - 1 : stage - 1, nk);
+        if (nk < KT)
+            lp.issue_all((stage == 0 ? NSTAGE - 1 : stage - 1) * Cfg::STAGE_BYTES,
+                         static_cast<size_t>(nk) * BK);
         mma_stage<Cfg>(smem + stage * Cfg::STAGE_BYTES, fp, acc);
         stage = (stage + 1 == NSTAGE) ? 0 : stage + 1;
     }
     store_tile<Cfg>(acc, tc, fp, wm, wn, C, N);
 }
 
-// ---- kernel 2: wavefront-specialised, two LDS stages ---------------------------------------
-// Wavefronts 0..NW-1 compute; NW loads the A tile, NW+1 the B tile, NW+2 prefetches into L2.
-// All of them meet at one barrier per k-step: after barrier kt the stage of k-step kt is
-// complete (the producers waited for their loads before arriving) and the other stage is free
-// (the consumers finished reading it before arriving), so the producers refill it with k-step
-// kt+1 while the consumers work on kt.
-constexpr int kWsExtraWaves = 3;
-constexpr int kPrefetchDist = 2;   // k-steps between the L2 touch and the direct-to-LDS load
+// ---- kernel 2: operand rings of different depth, hand-placed software pipeline ---------------
+// A k-step (64 k) is two half-steps of one MFMA k-substep each. While the MFMAs of a half-step
+// issue, the fragments of the next half-step are read from LDS into the registers that the
+// MFMAs just consumed. The barrier of k-step kt sits between its two half-steps: when a
+// wavefront arrives it has read all of k-step kt (the fragments of the second half are in
+// registers) and its loads of k-step kt+1 have landed, so after the barrier the stages of
+// k-step kt may be refilled and k-step kt+1 may be read, and the MFMAs of the second half-step
+// are ready to issue at once. Scheduling fences keep each group of MFMAs, LDS reads and
+// direct-to-LDS loads where it is written.
+//
+// LDS holds NA stages of the A tile and NB stages of the B tile (BM or BN rows of 64 k each;
+// for 256 x 256 tiles NA + NB = 5 stages of 32 KB fill the 160 KB). After the barrier of k-step
+// kt the A stage is refilled with k-step kt+NA and the B stage with k-step kt+NB, so the
+// operand with the deeper ring has NB-1 (or NA-1) k-steps to arrive: with two stages each the
+// kernel waits about a third of every k-step for the slowest cache line of the next one. The
+// operand with the shallower ring is issued first within a k-step: loads complete in order, so
+// the wait for it then leaves only the newest loads of the deeper operand pending.
+#define MOE_FENCE() __builtin_amdgcn_sched_barrier(0)
 
-template <class Cfg>
-__global__ __launch_bounds__(Cfg::NTHREADS + kWsExtraWaves * 64) void grouped_gemm_ws_kernel(
+template <class Cfg, int NA, int NB>
+struct RingCfg {
+    static constexpr int A_RING = NA * Cfg::A_BYTES, SMEM = NA * Cfg::A_BYTES + NB * Cfg::B_BYTES;
+    static constexpr bool A_FIRST = NA <= NB;                 // issue order inside a k-step
+    static constexpr int LA = Cfg::NIA / Cfg::NW, LB = Cfg::NIB / Cfg::NW;
+    // loads that may stay pending when k-step kt+1 must have landed
+    static constexpr int PENDING = (NA == NB) ? 0 : (NA < NB ? (NB - NA) * LB : (NA - NB) * LA);
+    static_assert(SMEM <= 160 * 1024 && NA >= 2 && NB >= 2, "LDS budget");
+    static_assert(NA - NB <= 1 && NB - NA <= 1, "pending count assumes rings that differ by one");
+};
+
+// One k-step. DMA_A / DMA_B: refill the freed stages (k-steps kt+NA / kt+NB exist); READ_NEXT:
+// k-step kt+1 exists. With RUNTIME the three flags are wave-uniform runtime values (tail of
+// the k-loop) and the wait is total.
+template <class Cfg, int NA, int NB, bool RUNTIME>
+__device__ __forceinline__ void ring_kstep(f32x4 (&acc)[Cfg::TM][Cfg::TN], bf16x8 (&fa)[Cfg::TM],
+                                           bf16x8 (&fb0)[Cfg::TN], bf16x8 (&fb1)[Cfg::TN],
+                                           const unsigned char* pa_h1, const unsigned char* pb_h1,
+                                           const unsigned char* pa_n0, const unsigned char* pb_n0,
+                                           const LoadPlan<Cfg>& lp, uint32_t a_region,
+                                           uint32_t b_region, size_t a_koff, size_t b_koff,
+                                           bool dma_a, bool dma_b, bool read_next) {
+    using R = RingCfg<Cfg, NA, NB>;
+    constexpr int TM = Cfg::TM, TN = Cfg::TN, LA = R::LA, LB = R::LB, LPW = LA + LB;
+    static_assert(TN <= TM && (LPW % TM == 0 || TM % LPW == 0), "interleave plan");
+    // ---- first half: MFMAs on (fa, fb0); read the second-half fragments of this k-step
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j) mma16_agpr(fb0[j], fa[i], acc[i][j]);
+        MOE_FENCE();
+        fa[i] = lds16(pa_h1 + i * Cfg::TILE_STEP);
+        if (i < TN) fb1[i] = lds16(pb_h1 + i * Cfg::TILE_STEP);
+        MOE_FENCE();
+    }
+    if (RUNTIME) asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" :: "n"(R::PENDING) : "memory");
+    __builtin_amdgcn_s_barrier();      // k-step kt+1 complete in LDS; this k-step's stages are free
+    MOE_FENCE();
+    // ---- second half: MFMAs on (fa, fb1); read the first-half fragments of k-step kt+1;
+    //      refill the freed stages
+    auto issue = [&](int n) {          // n-th load of this k-step in issue order
+        const bool is_a = R::A_FIRST ? (n < LA) : (n >= LB);
+        const int idx = R::A_FIRST ? (is_a ? n : n - LA) : (is_a ? n - LB : n);
+        if (is_a) { if (!RUNTIME || dma_a) lp.issue_a(idx, a_region, a_koff); }
+        else { if (!RUNTIME || dma_b) lp.issue_b(idx, b_region, b_koff); }
+    };
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j) mma16_agpr(fb1[j], fa[i], acc[i][j]);
+        MOE_FENCE();
+        if (!RUNTIME || read_next) {
+            fa[i] = lds16(pa_n0 + i * Cfg::TILE_STEP);
+            if (i < TN) fb0[i] = lds16(pb_n0 + i * Cfg::TILE_STEP);
+        }
+        if (LPW >= TM) {
+#pragma unroll
+            for (int n = 0; n < LPW / TM; ++n) issue(i * (LPW / TM) + n);
+        } else if (i % (TM / LPW) == 0) {
+            issue(i / (TM / LPW));
+        }
+        MOE_FENCE();
+    }
+}
+
+template <class Cfg, int NA, int NB>
+__global__ __launch_bounds__(Cfg::NTHREADS) void grouped_gemm_ring_kernel(
     const uint16_t* __restrict__ A, const uint16_t* __restrict__ B0,
     const uint16_t* __restrict__ B1, uint16_t* __restrict__ C,
     const int32_t* __restrict__ offsets, const int32_t* __restrict__ row_index, int index_div,
     int E, int N, int K) {
-    constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, WN = Cfg::WN, NW = Cfg::NW;
-    constexpr int TM = Cfg::TM, TN = Cfg::TN;
-    constexpr int CPR = Cfg::CPR, RPI = Cfg::RPI, NIA = Cfg::NIA, NIB = Cfg::NIB;
-    static_assert(Cfg::NSTAGE == 2, "the specialised kernel uses two stages");
-    static_assert(NIA <= 32 && NIB <= 32, "producer load count must fit the load counter");
+    using R = RingCfg<Cfg, NA, NB>;
+    constexpr int BM = Cfg::BM, BK = Cfg::BK, WN = Cfg::WN, TM = Cfg::TM, TN = Cfg::TN;
+    constexpr int LA = R::LA, LB = R::LB, AB = Cfg::A_BYTES, BB = Cfg::B_BYTES;
+    static_assert(BK == 64, "64-k stages");
 
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
@@ -366,91 +471,62 @@ __global__ __launch_bounds__(Cfg::NTHREADS + kWsExtraWaves * 64) void grouped_ge
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int KT = K / BK;
-
-    if (wave == NW + 2) {
-        // ---------------- L2 prefetch wavefront. The workgroups resident together on an XCD
-        // share every A row among the n-tiles of a group and every weight row among its gm
-        // m-tiles; each one touches its slice of those lines kPrefetchDist k-steps ahead with
-        // 4-byte loads whose results are never used (the counter is only bounded).
-        const int n_share = max(1, 32 / tc.gm);                // n-tiles resident per m-group
-        const int a_rows = (BM + n_share - 1) / n_share;       // <= BM
-        const int b_rows = (BN + tc.gm - 1) / tc.gm;           // <= BN
-        const int a0 = (tc.nt % n_share) * a_rows, b0 = tc.mi * b_rows;
-        uint32_t sink = 0;
-        for (int kt = 0; kt < KT; ++kt) {
-            __builtin_amdgcn_s_barrier();
-            const size_t ko = static_cast<size_t>(min(kt + kPrefetchDist, KT - 1)) * BK;
-            for (int r = 0; r < a_rows; r += 64) {
-                const int row = min(min(a0 + r + lane, a0 + a_rows - 1), tc.rows - 1);
-                const uint16_t* p = a_origin(A, tc, row_index, K) +
-                                    static_cast<size_t>(source_row(tc, row, row_index, index_div)) * K + ko;
-                asm volatile("global_load_dword %0, %1, off" : "+v"(sink) : "v"(p) : "memory");
-            }
-            for (int r = 0; r < b_rows; r += 64) {
-                const int row = min(min(b0 + r + lane, b0 + b_rows - 1), BN - 1);
-                const uint16_t* p = weight_row_ptr<Cfg>(tc, row, B0, B1, N, K) + ko;
-                asm volatile("global_load_dword %0, %1, off" : "+v"(sink) : "v"(p) : "memory");
-            }
-            wait_vmcnt<24>();
-        }
-        wait_vmcnt<0>();
-        asm volatile("" :: "v"(sink));
-        return;
-    }
-
-    if (wave >= NW) {
-        // ---------------- producer wavefronts. Load q of a tile covers tile rows
-        // [q*RPI, (q+1)*RPI); lane l lands at row q*RPI + l/CPR, chunk position l%CPR, so it
-        // fetches logical chunk (l%CPR) ^ swz(row). A rows past the group's end are clamped to
-        // its last row (always in bounds; masked at the store).
-        const bool is_b = (wave == NW + 1);
-        constexpr int NI = (NIA > NIB) ? NIA : NIB;
-        const int ni = is_b ? NIB : NIA;
-        const int lrow = lane / CPR, lpos = lane % CPR;
-        uint32_t voff[NI];
-#pragma unroll
-        for (int q = 0; q < NI; ++q) {
-            const int r = q * RPI + lrow;
-            const int rr = is_b ? lrow
-                                : source_row(tc, min(r, tc.rows - 1), row_index, index_div);
-            voff[q] = (static_cast<uint32_t>(rr) * K + ((lpos ^ swz<BK>(r)) * 8)) * 2u;
-        }
-        const uint16_t* a_base = a_origin(A, tc, row_index, K);
-        auto issue = [&](int stage, int kt) {
-            const uint32_t sbase = stage * Cfg::STAGE_BYTES + (is_b ? Cfg::A_BYTES : 0);
-            const size_t koff = static_cast<size_t>(kt) * BK;
-#pragma unroll
-            for (int q = 0; q < NI; ++q)
-                if (q < ni) {
-                    const uint16_t* base = is_b ? weight_row_ptr<Cfg>(tc, q * RPI, B0, B1, N, K) : a_base;
-                    dma16(base + koff, voff[q], sbase + q * 1024);
-                }
-        };
-        issue(0, 0);
-        for (int kt = 0; kt < KT; ++kt) {
-            wait_vmcnt<0>();                       // this wavefront's loads of k-step kt landed
-            __builtin_amdgcn_s_barrier();
-            if (kt + 1 < KT) issue((kt + 1) & 1, kt + 1);
-        }
-        return;                                    // nothing in flight: the last wait was total
-    }
-
-    // ---------------- consumer wavefronts
     const int wm = wave / WN, wn = wave % WN;
-    f32x16 acc[TM][TN];
+
+    LoadPlan<Cfg> lp;
+    lp.init(tc, wave, lane, A, B0, B1, row_index, index_div, N, K);
+    FragPlan<Cfg> fp;
+    fp.init(lane, wm, wn);
+    // fragment addresses of the two k-halves inside stage 0 of each ring
+    const unsigned char* pa[2] = {smem + fp.a_off[0], smem + fp.a_off[1]};
+    const unsigned char* pb[2] = {smem + R::A_RING + (fp.b_off[0] - AB), smem + R::A_RING + (fp.b_off[1] - AB)};
+
+    f32x4 acc[TM][TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
+        for (int j = 0; j < TN; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    mfma_drain();                                    // accumulator writes settle before MFMAs
+
+    const int KT = K / BK;                           // >= max(NA, NB) (checked by the launcher)
+    // prologue: fill both rings in the order the k-loop would have issued them
+    constexpr int NMAX = NA < NB ? NB : NA;
 #pragma unroll
-            for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.f;
-    FragPlan<Cfg> fp;
-    fp.init(lane, wm, wn);
-    for (int kt = 0; kt < KT; ++kt) {
-        __builtin_amdgcn_s_barrier();
-        mma_stage<Cfg>(smem + (kt & 1) * Cfg::STAGE_BYTES, fp, acc);
+    for (int s = 0; s < NMAX; ++s) {
+        const size_t koff = static_cast<size_t>(s) * BK;
+        if (R::A_FIRST) {
+            if (s < NA) for (int i = 0; i < LA; ++i) lp.issue_a(i, s * AB, koff);
+            if (s < NB) for (int i = 0; i < LB; ++i) lp.issue_b(i, R::A_RING + s * BB, koff);
+        } else {
+            if (s < NB) for (int i = 0; i < LB; ++i) lp.issue_b(i, R::A_RING + s * BB, koff);
+            if (s < NA) for (int i = 0; i < LA; ++i) lp.issue_a(i, s * AB, koff);
+        }
     }
+    constexpr int TOTAL = NA * LA + NB * LB;
+    wait_vmcnt<TOTAL - (LA + LB)>();                 // k-step 0 landed
+    __builtin_amdgcn_s_barrier();
+    bf16x8 fa[TM], fb0[TN], fb1[TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) fa[i] = lds16(pa[0] + i * Cfg::TILE_STEP);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) fb0[j] = lds16(pb[0] + j * Cfg::TILE_STEP);
+    MOE_FENCE();
+
+    int ra = 0, rb = 0;                              // ring positions of k-step kt
+    auto step = [&](auto runtime_tag, int kt) {
+        constexpr bool RT = decltype(runtime_tag)::value;
+        const int ra1 = (ra + 1 == NA) ? 0 : ra + 1, rb1 = (rb + 1 == NB) ? 0 : rb + 1;
+        ring_kstep<Cfg, NA, NB, RT>(acc, fa, fb0, fb1, pa[1] + ra * AB, pb[1] + rb * BB,
+                                    pa[0] + ra1 * AB, pb[0] + rb1 * BB, lp, ra * AB,
+                                    R::A_RING + rb * BB, static_cast<size_t>(kt + NA) * BK,
+                                    static_cast<size_t>(kt + NB) * BK, kt + NA < KT, kt + NB < KT,
+                                    kt + 1 < KT);
+        ra = ra1; rb = rb1;
+    };
+    int kt = 0;
+    for (; kt + NMAX < KT; ++kt) step(std::false_type{}, kt);
+    for (; kt < KT; ++kt) step(std::true_type{}, kt);
+    mfma_drain();
     store_tile<Cfg>(acc, tc, fp, wm, wn, C, N);
 }
 
