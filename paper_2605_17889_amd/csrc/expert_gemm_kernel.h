@@ -46,42 +46,68 @@ struct TileCoord {
     int gm;          // m-tiles in that group
 };
 
-// Map a workgroup to its tile. Logical tile order: expert by expert; inside an expert, groups
-// of kGroupM m-tiles; inside a group the n-tiles, each visited by all m-tiles of the group in
-// turn. XCD x is handed the x-th contiguous eighth of that order, so the workgroups resident
-// together on one XCD share A rows and weight tiles in its L2.
+// Map a workgroup to its tile. Full m-tiles (BM rows) come first, the partial last m-tiles of
+// the experts after them: a partial tile takes about half the time of a full one, and the
+// hardware starts workgroups in index order, so the cheap tiles fill the last, incomplete
+// round of the compute units. Logical order of the full tiles: expert by expert; inside an
+// expert, groups of kGroupM m-tiles; inside a group the n-tiles, each visited by all m-tiles of
+// the group in turn. XCD x is handed the x-th contiguous eighth of that order (and of the
+// partial tiles), so the workgroups resident together on one XCD share A rows and weight
+// tiles in its L2.
 template <int BM>
 __device__ __forceinline__ TileCoord locate_tile(const int32_t* __restrict__ offsets, int E,
                                                  int NT) {
     TileCoord tc{-1, 0, 0, 0, 0, 1};
-    int total = 0;
-    for (int e = 0; e < E; ++e) total += ((offsets[e + 1] - offsets[e] + BM - 1) / BM) * NT;
-    const int per = (total + kXcds - 1) / kXcds;
+    int total_full = 0, total_part = 0;
+    for (int e = 0; e < E; ++e) {
+        const int m_e = offsets[e + 1] - offsets[e];
+        total_full += (m_e / BM) * NT;
+        total_part += (m_e % BM != 0) ? NT : 0;
+    }
+    const int per_full = (total_full + kXcds - 1) / kXcds, per_part = (total_part + kXcds - 1) / kXcds;
     const int xcd = blockIdx.x % kXcds;
     const int slot = blockIdx.x / kXcds;
-    const int L = xcd * per + slot;
-    if (slot >= per || L >= total) return tc;
+    if (slot < per_full) {
+        const int L = xcd * per_full + slot;
+        if (L >= total_full) return tc;
+        int start = 0;
+        for (int e = 0; e < E; ++e) {
+            const int m_e = offsets[e + 1] - offsets[e];
+            const int mt = m_e / BM;
+            const int n_tiles = mt * NT;
+            if (L < start + n_tiles) {
+                const int local = L - start;
+                const int g = local / (kGroupM * NT);
+                const int first = g * kGroupM;
+                const int gm = min(kGroupM, mt - first);
+                const int in = local - g * (kGroupM * NT);
+                const int mi = first + in % gm;
+                tc.expert = e;
+                tc.mi = in % gm;
+                tc.gm = gm;
+                tc.nt = in / gm;
+                tc.row0 = offsets[e] + mi * BM;
+                tc.rows = BM;
+                return tc;
+            }
+            start += n_tiles;
+        }
+        return tc;
+    }
+    const int L = xcd * per_part + (slot - per_full);
+    if (slot - per_full >= per_part || L >= total_part) return tc;
     int start = 0;
     for (int e = 0; e < E; ++e) {
         const int m_e = offsets[e + 1] - offsets[e];
-        const int mt = (m_e + BM - 1) / BM;
-        const int n_tiles = mt * NT;
-        if (L < start + n_tiles) {
-            const int local = L - start;
-            const int g = local / (kGroupM * NT);
-            const int first = g * kGroupM;
-            const int gm = min(kGroupM, mt - first);
-            const int in = local - g * (kGroupM * NT);
-            const int mi = first + in % gm;
+        if (m_e % BM == 0) continue;
+        if (L < start + NT) {
             tc.expert = e;
-            tc.mi = in % gm;
-            tc.gm = gm;
-            tc.nt = in / gm;
-            tc.row0 = offsets[e] + mi * BM;
-            tc.rows = min(BM, m_e - mi * BM);
+            tc.nt = L - start;
+            tc.row0 = offsets[e] + (m_e / BM) * BM;
+            tc.rows = m_e % BM;
             return tc;
         }
-        start += n_tiles;
+        start += NT;
     }
     return tc;
 }
@@ -110,7 +136,10 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
     asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
 }
 
-__device__ __forceinline__ float silu(float a) { return a / (1.0f + __expf(-a)); }
+// SiLU with the hardware exponential and reciprocal (about 1 ulp each): the result is rounded
+// to bf16 right away, and the exact division costs three times as many instructions in the
+// epilogue of every gate/up tile.
+__device__ __forceinline__ float silu(float a) { return a * __builtin_amdgcn_rcpf(1.0f + __expf(-a)); }
 
 template <int BM_, int BN_, int BK_, int WM_, int WN_, int NSTAGE_, bool DUAL_>
 struct Config {
@@ -274,6 +303,7 @@ struct LoadPlan {
     const uint16_t* a_base;
     const uint16_t* b_base[LB];
     uint32_t a_voff[LA], a_lds[LA], b_voff[LB], b_lds[LB];
+    bool a_on[LA];      // false: every row of this A load lies past the end of the group
     __device__ __forceinline__ void init(const TileCoord& tc, int wave, int lane, const uint16_t* A,
                                          const uint16_t* B0, const uint16_t* B1,
                                          const int32_t* row_index, int index_div, int N, int K) {
@@ -286,6 +316,7 @@ struct LoadPlan {
             const int src = source_row(tc, min(r, tc.rows - 1), row_index, index_div);
             a_voff[i] = (static_cast<uint32_t>(src) * K + ((lpos ^ swz<Cfg::BK>(r)) * 8)) * 2u;
             a_lds[i] = q * 1024;
+            a_on[i] = q * Cfg::RPI < tc.rows;
         }
 #pragma unroll
         for (int i = 0; i < LB; ++i) {
@@ -395,52 +426,78 @@ struct RingCfg {
     static constexpr int PENDING = (NA == NB) ? 0 : (NA < NB ? (NB - NA) * LB : (NA - NB) * LA);
     static_assert(SMEM <= 160 * 1024 && NA >= 2 && NB >= 2, "LDS budget");
     static_assert(NA - NB <= 1 && NB - NA <= 1, "pending count assumes rings that differ by one");
+    static_assert(NA * LA + NB * LB < 64, "loads in flight must fit the 6-bit load counter");
 };
 
-// One k-step. DMA_A / DMA_B: refill the freed stages (k-steps kt+NA / kt+NB exist); READ_NEXT:
-// k-step kt+1 exists. With RUNTIME the three flags are wave-uniform runtime values (tail of
-// the k-loop) and the wait is total.
-template <class Cfg, int NA, int NB, bool RUNTIME>
+// One k-step of one wavefront.
+//   COMPUTE  false for a wavefront whose rows all lie past the end of a partial tile: it only
+//            issues its loads and meets the others at the barrier.
+//   PARTIAL  the tile has fewer than BM rows: A loads whose rows all lie past the end are
+//            skipped (what the MFMAs read there only reaches output rows that are never stored).
+//   RUNTIME  tail of the k-loop: dma_a / dma_b say whether k-steps kt+NA / kt+NB exist,
+//            read_next whether kt+1 does, and the wait for loads is total.
+//
+// Fragment registers: A tile i of the next half-step replaces fa[i] right after the MFMAs that
+// consumed it, except the last tile, which alternates between fa[TM-1] (first half-steps) and
+// fx (second half-steps) so that it can be read at the start of the half-step: no LDS read is
+// issued in the last chunk and the wait for all reads before the barrier costs nothing. B
+// fragments alternate between fb0 and fb1 and are read in the first chunks.
+template <class Cfg, int NA, int NB, bool COMPUTE, bool PARTIAL, bool RUNTIME>
 __device__ __forceinline__ void ring_kstep(f32x4 (&acc)[Cfg::TM][Cfg::TN], bf16x8 (&fa)[Cfg::TM],
-                                           bf16x8 (&fb0)[Cfg::TN], bf16x8 (&fb1)[Cfg::TN],
-                                           const unsigned char* pa_h1, const unsigned char* pb_h1,
-                                           const unsigned char* pa_n0, const unsigned char* pb_n0,
-                                           const LoadPlan<Cfg>& lp, uint32_t a_region,
-                                           uint32_t b_region, size_t a_koff, size_t b_koff,
-                                           bool dma_a, bool dma_b, bool read_next) {
+                                           bf16x8& fx, bf16x8 (&fb0)[Cfg::TN],
+                                           bf16x8 (&fb1)[Cfg::TN], const unsigned char* pa_h1,
+                                           const unsigned char* pb_h1, const unsigned char* pa_n0,
+                                           const unsigned char* pb_n0, const LoadPlan<Cfg>& lp,
+                                           uint32_t a_region, uint32_t b_region, size_t a_koff,
+                                           size_t b_koff, bool dma_a, bool dma_b, bool read_next) {
     using R = RingCfg<Cfg, NA, NB>;
     constexpr int TM = Cfg::TM, TN = Cfg::TN, LA = R::LA, LB = R::LB, LPW = LA + LB;
+    constexpr int BPC = (TN + TM / 2 - 1) / (TM / 2);      // B reads per chunk (first chunks)
     static_assert(TN <= TM && (LPW % TM == 0 || TM % LPW == 0), "interleave plan");
+    static_assert(!PARTIAL || R::A_FIRST, "skipping A loads needs the B loads to be the newest");
     // ---- first half: MFMAs on (fa, fb0); read the second-half fragments of this k-step
+    if (COMPUTE) {
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
+        for (int i = 0; i < TM; ++i) {
 #pragma unroll
-        for (int j = 0; j < TN; ++j) mma16_agpr(fb0[j], fa[i], acc[i][j]);
-        MOE_FENCE();
-        fa[i] = lds16(pa_h1 + i * Cfg::TILE_STEP);
-        if (i < TN) fb1[i] = lds16(pb_h1 + i * Cfg::TILE_STEP);
-        MOE_FENCE();
+            for (int j = 0; j < TN; ++j) mma16_agpr(fb0[j], fa[i], acc[i][j]);
+            MOE_FENCE();    // the reads below reuse the registers of fa[i]: after its MFMAs
+            if (i == 0) fx = lds16(pa_h1 + (TM - 1) * Cfg::TILE_STEP);
+            if (i < TM - 1) fa[i] = lds16(pa_h1 + i * Cfg::TILE_STEP);
+#pragma unroll
+            for (int b = i * BPC; b < (i + 1) * BPC && b < TN; ++b)
+                fb1[b] = lds16(pb_h1 + b * Cfg::TILE_STEP);
+            MOE_FENCE();
+        }
     }
     if (RUNTIME) asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
     else asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" :: "n"(R::PENDING) : "memory");
     __builtin_amdgcn_s_barrier();      // k-step kt+1 complete in LDS; this k-step's stages are free
     MOE_FENCE();
-    // ---- second half: MFMAs on (fa, fb1); read the first-half fragments of k-step kt+1;
-    //      refill the freed stages
+    // ---- second half: MFMAs on (fa[0..TM-2], fx, fb1); read the first-half fragments of k-step
+    //      kt+1; refill the freed stages
     auto issue = [&](int n) {          // n-th load of this k-step in issue order
         const bool is_a = R::A_FIRST ? (n < LA) : (n >= LB);
         const int idx = R::A_FIRST ? (is_a ? n : n - LA) : (is_a ? n - LB : n);
-        if (is_a) { if (!RUNTIME || dma_a) lp.issue_a(idx, a_region, a_koff); }
-        else { if (!RUNTIME || dma_b) lp.issue_b(idx, b_region, b_koff); }
+        if (is_a) {
+            if ((!RUNTIME || dma_a) && (!PARTIAL || lp.a_on[idx])) lp.issue_a(idx, a_region, a_koff);
+        } else {
+            if (!RUNTIME || dma_b) lp.issue_b(idx, b_region, b_koff);
+        }
     };
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
+        if (COMPUTE) {
 #pragma unroll
-        for (int j = 0; j < TN; ++j) mma16_agpr(fb1[j], fa[i], acc[i][j]);
-        MOE_FENCE();
-        if (!RUNTIME || read_next) {
-            fa[i] = lds16(pa_n0 + i * Cfg::TILE_STEP);
-            if (i < TN) fb0[i] = lds16(pb_n0 + i * Cfg::TILE_STEP);
+            for (int j = 0; j < TN; ++j) mma16_agpr(fb1[j], i == TM - 1 ? fx : fa[i], acc[i][j]);
+            MOE_FENCE();
+            if (!RUNTIME || read_next) {
+                if (i == 0) fa[TM - 1] = lds16(pa_n0 + (TM - 1) * Cfg::TILE_STEP);
+                if (i < TM - 1) fa[i] = lds16(pa_n0 + i * Cfg::TILE_STEP);
+#pragma unroll
+                for (int b = i * BPC; b < (i + 1) * BPC && b < TN; ++b)
+                    fb0[b] = lds16(pb_n0 + b * Cfg::TILE_STEP);
+            }
         }
         if (LPW >= TM) {
 #pragma unroll
@@ -489,43 +546,61 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void grouped_gemm_ring_kernel(
     mfma_drain();                                    // accumulator writes settle before MFMAs
 
     const int KT = K / BK;                           // >= max(NA, NB) (checked by the launcher)
-    // prologue: fill both rings in the order the k-loop would have issued them
     constexpr int NMAX = NA < NB ? NB : NA;
-#pragma unroll
-    for (int s = 0; s < NMAX; ++s) {
-        const size_t koff = static_cast<size_t>(s) * BK;
-        if (R::A_FIRST) {
-            if (s < NA) for (int i = 0; i < LA; ++i) lp.issue_a(i, s * AB, koff);
-            if (s < NB) for (int i = 0; i < LB; ++i) lp.issue_b(i, R::A_RING + s * BB, koff);
-        } else {
-            if (s < NB) for (int i = 0; i < LB; ++i) lp.issue_b(i, R::A_RING + s * BB, koff);
-            if (s < NA) for (int i = 0; i < LA; ++i) lp.issue_a(i, s * AB, koff);
-        }
-    }
-    constexpr int TOTAL = NA * LA + NB * LB;
-    wait_vmcnt<TOTAL - (LA + LB)>();                 // k-step 0 landed
-    __builtin_amdgcn_s_barrier();
-    bf16x8 fa[TM], fb0[TN], fb1[TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i) fa[i] = lds16(pa[0] + i * Cfg::TILE_STEP);
-#pragma unroll
-    for (int j = 0; j < TN; ++j) fb0[j] = lds16(pb[0] + j * Cfg::TILE_STEP);
-    MOE_FENCE();
 
-    int ra = 0, rb = 0;                              // ring positions of k-step kt
-    auto step = [&](auto runtime_tag, int kt) {
-        constexpr bool RT = decltype(runtime_tag)::value;
-        const int ra1 = (ra + 1 == NA) ? 0 : ra + 1, rb1 = (rb + 1 == NB) ? 0 : rb + 1;
-        ring_kstep<Cfg, NA, NB, RT>(acc, fa, fb0, fb1, pa[1] + ra * AB, pb[1] + rb * BB,
-                                    pa[0] + ra1 * AB, pb[0] + rb1 * BB, lp, ra * AB,
-                                    R::A_RING + rb * BB, static_cast<size_t>(kt + NA) * BK,
-                                    static_cast<size_t>(kt + NB) * BK, kt + NA < KT, kt + NB < KT,
-                                    kt + 1 < KT);
-        ra = ra1; rb = rb1;
+    auto run = [&](auto compute_tag, auto partial_tag) {
+        constexpr bool COMPUTE = decltype(compute_tag)::value, PARTIAL = decltype(partial_tag)::value;
+        // prologue: fill both rings in the order the k-loop would have issued them
+#pragma unroll
+        for (int s = 0; s < NMAX; ++s) {
+            const size_t koff = static_cast<size_t>(s) * BK;
+            if (R::A_FIRST) {
+                if (s < NA) for (int i = 0; i < LA; ++i) if (!PARTIAL || lp.a_on[i]) lp.issue_a(i, s * AB, koff);
+                if (s < NB) for (int i = 0; i < LB; ++i) lp.issue_b(i, R::A_RING + s * BB, koff);
+            } else {
+                if (s < NB) for (int i = 0; i < LB; ++i) lp.issue_b(i, R::A_RING + s * BB, koff);
+                if (s < NA) for (int i = 0; i < LA; ++i) lp.issue_a(i, s * AB, koff);
+            }
+        }
+        constexpr int TOTAL = NA * LA + NB * LB;
+        if (PARTIAL) wait_vmcnt<0>();                // fewer loads than TOTAL were issued
+        else wait_vmcnt<TOTAL - (LA + LB)>();        // k-step 0 landed
+        __builtin_amdgcn_s_barrier();
+        bf16x8 fa[TM], fx, fb0[TN], fb1[TN];
+        if (COMPUTE) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i) fa[i] = lds16(pa[0] + i * Cfg::TILE_STEP);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) fb0[j] = lds16(pb[0] + j * Cfg::TILE_STEP);
+            fx = fa[TM - 1];
+        }
+        MOE_FENCE();
+
+        int ra = 0, rb = 0;                          // ring positions of k-step kt
+        auto step = [&](auto runtime_tag, int kt) {
+            constexpr bool RT = decltype(runtime_tag)::value;
+            const int ra1 = (ra + 1 == NA) ? 0 : ra + 1, rb1 = (rb + 1 == NB) ? 0 : rb + 1;
+            ring_kstep<Cfg, NA, NB, COMPUTE, PARTIAL, RT>(
+                acc, fa, fx, fb0, fb1, pa[1] + ra * AB, pb[1] + rb * BB, pa[0] + ra1 * AB,
+                pb[0] + rb1 * BB, lp, ra * AB, R::A_RING + rb * BB,
+                static_cast<size_t>(kt + NA) * BK, static_cast<size_t>(kt + NB) * BK, kt + NA < KT,
+                kt + NB < KT, kt + 1 < KT);
+            ra = ra1; rb = rb1;
+        };
+        int kt = 0;
+        for (; kt + NMAX < KT; ++kt) step(std::false_type{}, kt);
+        for (; kt < KT; ++kt) step(std::true_type{}, kt);
     };
-    int kt = 0;
-    for (; kt + NMAX < KT; ++kt) step(std::false_type{}, kt);
-    for (; kt < KT; ++kt) step(std::true_type{}, kt);
+    using T = std::true_type;
+    using F = std::false_type;
+    if (tc.rows == BM) {
+        run(T{}, F{});
+    } else if (wm * Cfg::WTM < tc.rows) {
+        run(T{}, T{});
+    } else {
+        run(F{}, T{});                               // no row of this wavefront is in the tile
+        return;
+    }
     mfma_drain();
     store_tile<Cfg>(acc, tc, fp, wm, wn, C, N);
 }
