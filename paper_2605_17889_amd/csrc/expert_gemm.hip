@@ -45,10 +45,8 @@ int launch_grouped(const moe_bf16* A, const moe_bf16* B0, const moe_bf16* B1, mo
             return MOE_ERR_HIP;
         attr_set = true;
     }
-    // full tiles <= (R / BM) * NT and partial tiles <= E * NT; each of the two ranges is dealt
-    // to the XCDs in eighths that are rounded up
-    const long long max_mt = R / Cfg::BM + E;
-    long long grid = max_mt * (N / Cfg::BN_OUT) + 2 * gemm::kXcds;
+    const long long max_mt = R / Cfg::BM + E;                  // >= sum_e ceil(M_e / BM)
+    long long grid = max_mt * (N / Cfg::BN_OUT);
     grid = (grid + gemm::kXcds - 1) / gemm::kXcds * gemm::kXcds;
     if (grid > 0x7fffffffLL) return MOE_ERR_UNSUPPORTED_SHAPE;
     hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(grid)), dim3(kThreads), smem, s,

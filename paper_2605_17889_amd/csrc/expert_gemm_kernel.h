@@ -46,68 +46,42 @@ struct TileCoord {
     int gm;          // m-tiles in that group
 };
 
-// Map a workgroup to its tile. Full m-tiles (BM rows) come first, the partial last m-tiles of
-// the experts after them: a partial tile takes about half the time of a full one, and the
-// hardware starts workgroups in index order, so the cheap tiles fill the last, incomplete
-// round of the compute units. Logical order of the full tiles: expert by expert; inside an
-// expert, groups of kGroupM m-tiles; inside a group the n-tiles, each visited by all m-tiles of
-// the group in turn. XCD x is handed the x-th contiguous eighth of that order (and of the
-// partial tiles), so the workgroups resident together on one XCD share A rows and weight
-// tiles in its L2.
+// Map a workgroup to its tile. Logical tile order: expert by expert; inside an expert, groups
+// of kGroupM m-tiles; inside a group the n-tiles, each visited by all m-tiles of the group in
+// turn. XCD x is handed the x-th contiguous eighth of that order, so the workgroups resident
+// together on one XCD share A rows and weight tiles in its L2.
 template <int BM>
 __device__ __forceinline__ TileCoord locate_tile(const int32_t* __restrict__ offsets, int E,
                                                  int NT) {
     TileCoord tc{-1, 0, 0, 0, 0, 1};
-    int total_full = 0, total_part = 0;
-    for (int e = 0; e < E; ++e) {
-        const int m_e = offsets[e + 1] - offsets[e];
-        total_full += (m_e / BM) * NT;
-        total_part += (m_e % BM != 0) ? NT : 0;
-    }
-    const int per_full = (total_full + kXcds - 1) / kXcds, per_part = (total_part + kXcds - 1) / kXcds;
+    int total = 0;
+    for (int e = 0; e < E; ++e) total += ((offsets[e + 1] - offsets[e] + BM - 1) / BM) * NT;
+    const int per = (total + kXcds - 1) / kXcds;
     const int xcd = blockIdx.x % kXcds;
     const int slot = blockIdx.x / kXcds;
-    if (slot < per_full) {
-        const int L = xcd * per_full + slot;
-        if (L >= total_full) return tc;
-        int start = 0;
-        for (int e = 0; e < E; ++e) {
-            const int m_e = offsets[e + 1] - offsets[e];
-            const int mt = m_e / BM;
-            const int n_tiles = mt * NT;
-            if (L < start + n_tiles) {
-                const int local = L - start;
-                const int g = local / (kGroupM * NT);
-                const int first = g * kGroupM;
-                const int gm = min(kGroupM, mt - first);
-                const int in = local - g * (kGroupM * NT);
-                const int mi = first + in % gm;
-                tc.expert = e;
-                tc.mi = in % gm;
-                tc.gm = gm;
-                tc.nt = in / gm;
-                tc.row0 = offsets[e] + mi * BM;
-                tc.rows = BM;
-                return tc;
-            }
-            start += n_tiles;
-        }
-        return tc;
-    }
-    const int L = xcd * per_part + (slot - per_full);
-    if (slot - per_full >= per_part || L >= total_part) return tc;
+    const int L = xcd * per + slot;
+    if (slot >= per || L >= total) return tc;
     int start = 0;
     for (int e = 0; e < E; ++e) {
         const int m_e = offsets[e + 1] - offsets[e];
-        if (m_e % BM == 0) continue;
-        if (L < start + NT) {
+        const int mt = (m_e + BM - 1) / BM;
+        const int n_tiles = mt * NT;
+        if (L < start + n_tiles) {
+            const int local = L - start;
+            const int g = local / (kGroupM * NT);
+            const int first = g * kGroupM;
+            const int gm = min(kGroupM, mt - first);
+            const int in = local - g * (kGroupM * NT);
+            const int mi = first + in % gm;
             tc.expert = e;
-            tc.nt = L - start;
-            tc.row0 = offsets[e] + (m_e / BM) * BM;
-            tc.rows = m_e % BM;
+            tc.mi = in % gm;
+            tc.gm = gm;
+            tc.nt = in / gm;
+            tc.row0 = offsets[e] + mi * BM;
+            tc.rows = min(BM, m_e - mi * BM);
             return tc;
         }
-        start += NT;
+        start += n_tiles;
     }
     return tc;
 }
