@@ -27,7 +27,7 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E peak
 # scaled by what the same counter reads for a plain 1 GiB copy: 2.00 and 1.00). Measured with the
 # commands recorded in profiles/expert_gemm_mixtral8x22b_prefill_hbm_traffic.md; it cannot be
 # measured from inside this process, so workloads without a recorded value report null.
-MEASURED_TRAFFIC_BYTES = {"mixtral8x22b_prefill": 11.36e9 + 0.537e9}
+MEASURED_TRAFFIC_BYTES = {"mixtral8x22b_prefill": 13.42e9 + 0.557e9}
 
 
 def log(*a):
@@ -169,7 +169,7 @@ def main():
     dom_launch_ms = dom["ms_per_step"] / max(dom["launches_per_step"], 1)
     dom_flops_per_launch = model["gateup"]["flops"] / max(dom["launches_per_step"], 1)
     achieved = dom_flops_per_launch / (dom_launch_ms * 1e-3) / 1e12
-    roofline = {"kernel": "grouped_gemm_kernel<gate/up, fused SiLU*mul>", "bound": "mfma",
+    roofline = {"kernel": "grouped_gemm_ring_kernel<gate/up, fused SiLU*mul>", "bound": "mfma",
                 "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": achieved / PEAK_BF16_TFLOPS,
                 "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name) if args.micro == 0 else None,
