@@ -358,3 +358,47 @@ def test_zipf_calibration_with_oracle_router():
     assert np.all(np.abs(counts[live] - target[live]) <= 0.02 * target[live] + 2)
     srt = np.sort(target[live])[::-1]
     assert np.allclose(srt / srt[0], np.arange(1, 8) ** -1.2, rtol=1e-12)
+
+
+# ------------------------------------------------------------------------- roofline cost model
+def test_cost_model_hand_values():
+    """Eq. 5 / Eq. 9 with Table 1 row 3, against values worked out by hand."""
+    from oracle.cost_model import expert_stage_estimate as est
+    # one expert, 1000 rows, d_h = 1000, d_e = 2000, device 1 TFLOP/s and 1 GB/s:
+    # D_X = 2e6 B, D_Y = 12e6 B, C = 12e9 FLOP -> memory 14e6/1e9 = 0.014 s, compute 0.012 s
+    o = est([[1000]], 1000, 2000, 1.0, 1.0)
+    assert o["flops"] == 12e9 and o["operand_bytes"] == 14e6
+    assert abs(o["t_stage_s"] - 0.014) < 1e-15 and abs(o["t_per_expert_s"] - 0.014) < 1e-15
+    assert o["memory_bound_instances"] == 1 and o["expert_instances"] == 1
+    # same expert on a 0.5 TFLOP/s device: compute 0.024 s wins
+    o = est([[1000]], 1000, 2000, 0.5, 1.0)
+    assert abs(o["t_stage_s"] - 0.024) < 1e-15 and o["memory_bound_instances"] == 0
+    # ridge: (2 r d + 6 d f)/BW = 6 r d f/TF  ->  r = 12e6/1e9 / (12e6/1e12 - 2e3/1e9) = 1200
+    assert abs(est([[1]], 1000, 2000, 1.0, 1.0)["ridge_rows"] - 1200.0) < 1e-9
+    # two experts (300 and 0 rows) in each of 2 micro-batches: empty experts cost nothing, M = 2 doubles
+    a = est([[300, 0]], 1000, 2000, 1.0, 1.0)
+    b = est([[300, 0], [300, 0]], 1000, 2000, 1.0, 1.0)
+    assert a["expert_instances"] == 1 and b["expert_instances"] == 2
+    assert abs(b["t_stage_s"] - 2 * a["t_stage_s"]) < 1e-18 and b["micro_batches"] == 2
+    # stage form never exceeds the per-expert form (max of sums <= sum of maxes)
+    c = est([[5000, 10]], 1000, 2000, 1.0, 1.0)
+    assert c["t_stage_s"] <= c["t_per_expert_s"] + 1e-18
+    # 5000 rows: compute 0.06 s vs memory 0.022 s; 10 rows: memory 0.01202 s vs compute 0.00012 s
+    assert abs(c["t_per_expert_s"] - (0.06 + 0.01202)) < 1e-12
+    assert abs(c["t_stage_s"] - max((10e6 + 12e6 + 2e4 + 12e6) / 1e9, 0.06012)) < 1e-12
+
+
+def test_cost_model_benchmark_floors():
+    """The floors quoted for the benchmark shapes: 8x22B prefill 9.896 TFLOP -> 3.958 ms at
+    2.5 PFLOP/s; 8x7B decode 2.819 GB of weights -> 352 us at 8 TB/s; 16 micro-batches of 256
+    tokens re-read 16 x 4.832 GB -> 9.66 ms."""
+    from oracle.cost_model import expert_stage_estimate as est
+    o = est([[2048] * 8], 6144, 16384, 2500.0, 8000.0)
+    assert abs(o["flops"] / 1e12 - 9.896) < 1e-3 and abs(o["t_stage_s"] * 1e3 - 3.958) < 1e-3
+    assert o["memory_bound_instances"] == 0 and 300 < o["ridge_rows"] < 330
+    o = est([[64] * 8], 4096, 14336, 2500.0, 8000.0)
+    assert abs(o["operand_bytes"] / 1e9 - (2.819 + 8 * 64 * 4096 * 2 / 1e9)) < 1e-3
+    assert abs(o["t_stage_s"] * 1e6 - 352.9) < 0.5 and o["memory_bound_instances"] == 8
+    o = est([[64] * 8] * 16, 6144, 16384, 2500.0, 8000.0)
+    assert abs(o["t_stage_s"] * 1e3 - 16 * (4.832e9 + 8 * 64 * 6144 * 2) / 8e12 * 1e3) < 1e-3
+    assert 9.66 < o["t_stage_s"] * 1e3 < 9.69 and o["memory_bound_instances"] == 128
