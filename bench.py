@@ -78,6 +78,54 @@ def cpu_baseline(cfg, L, target_seconds=15.0):
                       f"the oracle), {dt:.2f} s wall, double precision, OpenMP over tokens"}
 
 
+SUSTAINED_TFLOPS = 1330.0      # this library's gate/up kernel on large uniform expert groups
+SUSTAINED_GBS = 5400.0         # this library's weight streaming at 64 rows per expert
+
+
+def planner_sweep(args, cfg, L, ctx, y, B, torch):
+    """Measured expert-GEMM time per micro-batch size against the Eq. 5 / Eq. 9 estimate."""
+    T, E, k = cfg.T, cfg.E, cfg.k
+    idx = torch.empty((T, k), dtype=torch.int32, device="cuda")
+    w = torch.empty((T, k), dtype=torch.float32, device="cuda")
+    B.moe_route(ctx, L["x"], L["w_router"], L["bias"], T, idx, w)
+    torch.cuda.synchronize()
+    idx_host = idx.cpu()
+    sizes = [m for m in (64, 128, 256, 512, 1024, 2048, 4096, 8192) if m < T] + [T]
+    print(f"| micro-batch tokens | micro-batches | rows per expert (mean) | memory-bound expert "
+          f"instances | measured gate/up + down (ms) | TFLOP/s | estimate at peak "
+          f"({PEAK_BF16_TFLOPS:.0f} TFLOP/s, {PEAK_HBM_GBS:.0f} GB/s) (ms) | estimate at sustained "
+          f"rates ({SUSTAINED_TFLOPS:.0f} TFLOP/s, {SUSTAINED_GBS:.0f} GB/s) (ms) | measured / "
+          f"sustained estimate |")
+    print("|---|---|---|---|---|---|---|---|---|")
+    for m in sizes:
+        rows = [torch.bincount(idx_host[t0:t0 + m].reshape(-1).long(), minlength=E).tolist()
+                for t0 in range(0, T, m)]
+        steps = max(3, min(20, int(40 * m / T)))
+
+        def step():
+            if m < T:
+                B.moe_layer_forward_microbatched(ctx, L["x"], L["w_router"], L["bias"], L["W1"],
+                                                 L["W3"], L["W2"], T, m, y)
+            else:
+                B.moe_layer_forward(ctx, L["x"], L["w_router"], L["bias"], L["W1"], L["W3"],
+                                    L["W2"], T, y)
+        for _ in range(2):
+            step()
+        torch.cuda.synchronize()
+        B.moe_profile_begin(ctx, steps)
+        for _ in range(steps):
+            step()
+        torch.cuda.synchronize()
+        stage_ms, _, calls = B.moe_profile_end(ctx)
+        ms = (stage_ms["gateup"] + stage_ms["down"]) / max(calls, 1)
+        peak = B.moe_estimate_expert_stage(cfg.d_model, cfg.d_ff, rows, PEAK_BF16_TFLOPS, PEAK_HBM_GBS)
+        sus = B.moe_estimate_expert_stage(cfg.d_model, cfg.d_ff, rows, SUSTAINED_TFLOPS, SUSTAINED_GBS)
+        print(f"| {m} | {len(rows)} | {T * k / E / len(rows):.0f} | "
+              f"{peak['memory_bound_instances']} of {peak['expert_instances']} | {ms:.3f} | "
+              f"{peak['flops'] / (ms * 1e-3) / 1e12:.0f} | {peak['t_kernels_s'] * 1e3:.3f} | "
+              f"{sus['t_kernels_s'] * 1e3:.3f} | {ms / (sus['t_kernels_s'] * 1e3):.2f} |", flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -87,6 +135,13 @@ def main():
     ap.add_argument("--micro", type=int, default=0,
                     help="run the micro-batched call with this many tokens per micro-batch")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--gemm-config", type=int, default=-1,
+                    help="force the expert-GEMM tile configuration (0 large, 1 medium, 2 small); "
+                         "-1 = automatic")
+    ap.add_argument("--planner-sweep", action="store_true",
+                    help="run the workload coalesced and as micro-batches of 64..T/2 tokens and "
+                         "print, per micro-batch size, the measured expert-GEMM time next to the "
+                         "roofline estimate of moe_estimate_expert_stage (markdown table)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy 10 times (to scale rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE counters against a kernel of known traffic)")
@@ -114,6 +169,7 @@ def main():
         return
     cfg = synth.PRESETS[args.workload]
     T = cfg.T
+    B.moe_set_gemm_config(args.gemm_config)
     log(f"[bench] generating {cfg.name}: T={T} d={cfg.d_model} f={cfg.d_ff} E={cfg.E} k={cfg.k}")
     L = synth.make_layer(cfg, "cuda")
     ctx = B.MoeContext(T, cfg.d_model, cfg.d_ff, cfg.E, cfg.k)
@@ -127,6 +183,10 @@ def main():
 
         L["bias"] = synth.calibrate_expert_bias(cfg, count_fn).cuda()
     y = torch.empty((T, cfg.d_model), dtype=torch.bfloat16, device="cuda")
+    if args.planner_sweep:
+        planner_sweep(args, cfg, L, ctx, y, B, torch)
+        ctx.close()
+        return
 
     def step():
         if args.micro > 0:

@@ -160,6 +160,38 @@ int moe_last_routing(moe_ctx* ctx, int32_t T, int32_t* topk_idx, float* topk_w, 
 int moe_profile_begin(moe_ctx* ctx, int32_t max_calls);
 int moe_profile_end(moe_ctx* ctx, double* stage_ms, int64_t* stage_launches, int32_t* calls);
 
+/* Roofline estimate of the expert stage, host arithmetic only (no GPU is touched).
+ * Paper Table 1, row 3: per expert D_X = 2*rows*d_h and D_Y = 6*d_h*d_e operand bytes and
+ * C = 6*rows*d_h*d_e FLOP (bf16); Eq. 5: an operation costs M * max((D_X + D_Y) / BW, C / TF)
+ * over its M micro-batches; Eq. 9 applies that form to the whole expert stage of a device.
+ * The table's 2BLd_h/E is the uniform-routing average: here every expert has its own count.
+ *   rows [micro_batches * E] int32, HOST: rows routed to expert e in micro-batch m at
+ *   rows[m*E + e] (coalesced execution: micro_batches = 1); an expert with 0 rows costs nothing.
+ *   machine: the rates to price against (peaks, or rates measured on the device).
+ * Only d_model, d_ff and E of `shape` are used (any positive values). Returns
+ * MOE_ERR_INVALID_ARG for null pointers, negative counts or non-positive rates. */
+typedef struct {
+    double tflops;                  /* TF_DEV of Eq. 5, in 1e12 FLOP/s */
+    double gbytes_per_s;            /* BW_DEV of Eq. 5, in 1e9 byte/s */
+} moe_machine;
+
+typedef struct {
+    int32_t micro_batches;          /* M */
+    int32_t expert_instances;       /* (micro-batch, expert) pairs with at least one row */
+    int32_t memory_bound_instances; /* of those, the ones with (D_X + D_Y)/BW > C/TF */
+    double flops;                   /* sum of C */
+    double operand_bytes;           /* sum of D_X + D_Y */
+    double intermediate_bytes;      /* H written and read, outputs written (not in Table 1) */
+    double t_stage_s;               /* Eq. 9 per micro-batch: max(sum bytes/BW, sum C/TF), summed */
+    double t_per_expert_s;          /* Eq. 5 expert by expert, summed (experts one after another) */
+    double t_kernels_s;             /* gate/up and down as two grouped contractions per micro-batch,
+                                       each max(bytes/BW, FLOP/TF) with H counted */
+    double ridge_rows;              /* rows per expert above which an expert is compute-bound */
+} moe_expert_estimate;
+
+int moe_estimate_expert_stage(const moe_shape* shape, const int32_t* rows, int32_t micro_batches,
+                              const moe_machine* machine, moe_expert_estimate* out);
+
 /* Tuning / testing knob, process-wide: force the expert-GEMM tile configuration
  * (0 = large, 1 = medium, 2 = small rows-per-expert tile) or -1 for the automatic choice by
  * average rows per expert. Every configuration produces identical bits (same accumulation

@@ -22,13 +22,25 @@ EXPORTS = (
     "moe_create", "moe_destroy", "moe_workspace_bytes", "moe_status_string", "moe_route",
     "moe_route_from_logits", "moe_permute", "moe_expert_ffn", "moe_combine", "moe_layer_forward",
     "moe_layer_forward_microbatched", "moe_last_routing", "moe_profile_begin", "moe_profile_end",
-    "moe_set_gemm_config",
+    "moe_set_gemm_config", "moe_estimate_expert_stage",
 )
 
 
 class MoeShape(C.Structure):
     _fields_ = [("T_max", C.c_int32), ("d_model", C.c_int32), ("d_ff", C.c_int32),
                 ("E", C.c_int32), ("k", C.c_int32)]
+
+
+class MoeMachine(C.Structure):
+    _fields_ = [("tflops", C.c_double), ("gbytes_per_s", C.c_double)]
+
+
+class MoeExpertEstimate(C.Structure):
+    _fields_ = [("micro_batches", C.c_int32), ("expert_instances", C.c_int32),
+                ("memory_bound_instances", C.c_int32), ("flops", C.c_double),
+                ("operand_bytes", C.c_double), ("intermediate_bytes", C.c_double),
+                ("t_stage_s", C.c_double), ("t_per_expert_s", C.c_double),
+                ("t_kernels_s", C.c_double), ("ridge_rows", C.c_double)]
 
 
 class MoeError(RuntimeError):
@@ -198,6 +210,20 @@ def moe_profile_end(ctx: MoeContext):
     _check(lib().moe_profile_end(ctx._h, ms, launches, C.byref(calls)), "moe_profile_end")
     return ({s: ms[i] for i, s in enumerate(STAGES)},
             {s: launches[i] for i, s in enumerate(STAGES)}, calls.value)
+
+
+def moe_estimate_expert_stage(d_model: int, d_ff: int, rows, tflops: float, gbytes_per_s: float) -> dict:
+    """rows: host sequence [micro_batches][E] of routed row counts. Host arithmetic only."""
+    micro_batches = len(rows)
+    E = len(rows[0]) if micro_batches else 1
+    flat = (C.c_int32 * max(1, micro_batches * E))(*[int(v) for mb in rows for v in mb])
+    shape = MoeShape(0, d_model, d_ff, E, 1)
+    machine = MoeMachine(tflops, gbytes_per_s)
+    out = MoeExpertEstimate()
+    _check(lib().moe_estimate_expert_stage(C.byref(shape), flat, C.c_int32(micro_batches),
+                                           C.byref(machine), C.byref(out)),
+           "moe_estimate_expert_stage")
+    return {name: getattr(out, name) for name, _ in MoeExpertEstimate._fields_}
 
 
 def moe_set_gemm_config(config: int):

@@ -10,6 +10,8 @@
 // tile). Every output element is one accumulator chain over k = 0,16,32,... with the same
 // MFMA instruction in every tile configuration, so results do not depend on how many rows an
 // expert has or which configuration is picked (coalesced == micro-batched, bit for bit).
+#include <cmath>
+
 #include "expert_gemm_kernel.h"
 
 namespace moe {
@@ -59,13 +61,18 @@ int g_forced_config = -1;   // -1: automatic; 0,1,2: force (tests / tuning)
 
 int pick_config(int R, int E) {
     if (g_forced_config >= 0) return g_forced_config;
-    // 0: compute-bound groups (pipelined 256x256 tiles). 1: groups of up to ~128
-    // rows: the kernel streams the weights once per 128-row m-tile and is HBM-bound. 2: a few
-    // rows per expert (64-row tiles).
-    const int avg = R / (E > 0 ? E : 1);
-    if (avg >= 192) return 0;
-    if (avg > 32) return 1;
-    return 2;
+    // 0: pipelined 256x256 tiles. 1: 128-row tiles (generic kernel). 2: a few rows per expert
+    // (64-row tiles). Between 0 and 1 the padded rows decide: groups a little above a multiple
+    // of 256 rows waste most of a large tile. Per-expert counts are not known on the host, so
+    // the choice prices the average group plus two standard deviations of a uniform routing,
+    // and the large tiles at 0.8 of the time per padded row of the 128-row ones (measured on
+    // micro-batches of 64 to 4096 tokens at the 8x22B shape).
+    const double avg = static_cast<double>(R) / (E > 0 ? E : 1);
+    if (avg <= 32.0) return 2;
+    const double upper = avg + 2.0 * std::sqrt(avg);
+    const double padded_large = std::ceil(upper / 256.0) * 256.0;
+    const double padded_mid = std::ceil(upper / 128.0) * 128.0;
+    return padded_large * 0.8 <= padded_mid ? 0 : 1;
 }
 
 //                      BM   BN  BK WM WN NSTAGE DUAL
