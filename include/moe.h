@@ -20,9 +20,9 @@
  *   - T = 0 is legal and a no-op. An expert that receives no row is legal.
  *   - A context is bound to one device and must be used from one stream at a time: its
  *     workspace is shared by consecutive calls.
- *   - Supported shapes: d_model a multiple of 512, d_ff a multiple of 256,
- *     1 <= k <= E <= 64, 0 <= T <= T_max, T_max * k < 2^31 (row offsets into the tensors are
- *     64-bit inside the kernels). Anything else is MOE_ERR_UNSUPPORTED_SHAPE.
+ *   - Supported shapes: d_model a multiple of 512, d_ff a multiple of 128,
+ *     1 <= k <= min(E, 64), E <= 256, 0 <= T <= T_max, T_max * k < 2^31 (row offsets into the
+ *     tensors are 64-bit inside the kernels). Anything else is MOE_ERR_UNSUPPORTED_SHAPE.
  *
  * Weight layout (out, in): W1, W3 are [E, d_ff, d_model]; W2 is [E, d_model, d_ff]; the
  * router matrix is [d_model, E] fp32. These are the three d_h x d_e bf16 matrices per expert

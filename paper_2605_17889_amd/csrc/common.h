@@ -8,7 +8,7 @@
 namespace moe {
 
 constexpr int kWave = 64;        // CDNA wavefront width
-constexpr int kMaxExperts = 64;  // one lane per expert in the permutation kernels
+constexpr int kMaxExperts = 256; // four experts per lane in the permutation and routing kernels
 
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) {
     return __uint_as_float(static_cast<uint32_t>(b) << 16);
@@ -30,7 +30,8 @@ __device__ __forceinline__ uint16_t f32_to_bf16(float f) {
 
 // Launch wrappers (defined in the .hip files). Each returns a moe_status and only enqueues.
 int launch_route(const moe_bf16* x, const float* w_router, const float* bias, int T, int d, int E,
-                 int k, int32_t* topk_idx, float* topk_w, float* logits_out, hipStream_t s);
+                 int k, int32_t* topk_idx, float* topk_w, float* logits_out,
+                 float* logits_scratch, hipStream_t s);
 int launch_route_from_logits(const float* logits, int T, int E, int k, int32_t* topk_idx,
                              float* topk_w, hipStream_t s);
 size_t permute_scratch_ints(int R_max, int E);

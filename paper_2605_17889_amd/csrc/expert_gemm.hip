@@ -96,7 +96,9 @@ int launch_gateup(const moe_bf16* a, const int32_t* row_index, int index_div,
                   const moe_bf16* W3, moe_bf16* H, hipStream_t s) {
     if (R == 0) return MOE_OK;
     const moe_bf16* x_perm = a;
-    switch (pick_config(R, E)) {
+    int config = pick_config(R, E);
+    if (config == 0 && d / 64 < 3) config = 1;     // the pipelined kernel needs three k-steps
+    switch (config) {
         case 0: return launch_grouped<GateUpLarge, 2, 3>(x_perm, W1, W3, H, offsets, row_index, index_div, R, E, f, d, s);
         case 1: return launch_grouped<GateUpMid>(x_perm, W1, W3, H, offsets, row_index, index_div, R, E, f, d, s);
         default: return launch_grouped<GateUpSmall>(x_perm, W1, W3, H, offsets, row_index, index_div, R, E, f, d, s);
@@ -106,7 +108,9 @@ int launch_gateup(const moe_bf16* a, const int32_t* row_index, int index_div,
 int launch_down(const moe_bf16* H, const int32_t* offsets, int R, int d, int f, int E,
                 const moe_bf16* W2, moe_bf16* y_perm, hipStream_t s) {
     if (R == 0) return MOE_OK;
-    switch (pick_config(R, E)) {
+    int config = pick_config(R, E);
+    if (config == 0 && f / 64 < 3) config = 1;     // the pipelined kernel needs three k-steps
+    switch (config) {
         case 0: return launch_grouped<DownLarge, 2, 3>(H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
         case 1:
             // HBM-bound: wide tiles stream more bytes per workgroup, but only if there are

@@ -50,38 +50,68 @@ struct TileCoord {
 // of kGroupM m-tiles; inside a group the n-tiles, each visited by all m-tiles of the group in
 // turn. XCD x is handed the x-th contiguous eighth of that order, so the workgroups resident
 // together on one XCD share A rows and weight tiles in its L2.
+//
+// Every wavefront works the map out by itself, without LDS: lane l takes experts l, l+64, ...
+// (one vector load of their offsets), the tile counts are prefix-summed across the lanes, and
+// the lane whose range holds the tile number broadcasts its expert. The cost does not grow
+// with the number of experts (a scalar loop over 128 experts would cost more than a tile of a
+// small expert).
 template <int BM>
 __device__ __forceinline__ TileCoord locate_tile(const int32_t* __restrict__ offsets, int E,
                                                  int NT) {
+    constexpr int EW = kMaxExperts / kWave;
     TileCoord tc{-1, 0, 0, 0, 0, 1};
-    int total = 0;
-    for (int e = 0; e < E; ++e) total += ((offsets[e + 1] - offsets[e] + BM - 1) / BM) * NT;
+    const int lane = threadIdx.x & (kWave - 1);
+    int rows[EW], first[EW], tiles[EW], incl[EW];     // per expert of this lane; incl: prefix sum
+    int carry = 0;
+#pragma unroll
+    for (int w = 0; w < EW; ++w) {
+        const int e = w * kWave + lane;
+        rows[w] = first[w] = tiles[w] = incl[w] = 0;
+        if (w * kWave >= E) continue;                  // uniform
+        if (e < E) {
+            first[w] = offsets[e];
+            rows[w] = offsets[e + 1] - first[w];
+            tiles[w] = ((rows[w] + BM - 1) / BM) * NT;
+        }
+        int sum = tiles[w];
+#pragma unroll
+        for (int s = 1; s < kWave; s <<= 1) {
+            const int up = __shfl_up(sum, s, kWave);
+            if (lane >= s) sum += up;
+        }
+        incl[w] = carry + sum;
+        carry += __shfl(sum, kWave - 1, kWave);
+    }
+    const int total = __builtin_amdgcn_readfirstlane(carry);
     const int per = (total + kXcds - 1) / kXcds;
     const int xcd = blockIdx.x % kXcds;
     const int slot = blockIdx.x / kXcds;
     const int L = xcd * per + slot;
     if (slot >= per || L >= total) return tc;
-    int start = 0;
-    for (int e = 0; e < E; ++e) {
-        const int m_e = offsets[e + 1] - offsets[e];
+#pragma unroll
+    for (int w = 0; w < EW; ++w) {
+        if (w * kWave >= E) continue;
+        const uint64_t hit = __ballot(tiles[w] > 0 && L >= incl[w] - tiles[w] && L < incl[w]);
+        if (hit == 0) continue;                        // uniform
+        const int src = __builtin_ctzll(hit);
+        const int start = __builtin_amdgcn_readfirstlane(__shfl(incl[w] - tiles[w], src, kWave));
+        const int m_e = __builtin_amdgcn_readfirstlane(__shfl(rows[w], src, kWave));
+        const int row_e = __builtin_amdgcn_readfirstlane(__shfl(first[w], src, kWave));
         const int mt = (m_e + BM - 1) / BM;
-        const int n_tiles = mt * NT;
-        if (L < start + n_tiles) {
-            const int local = L - start;
-            const int g = local / (kGroupM * NT);
-            const int first = g * kGroupM;
-            const int gm = min(kGroupM, mt - first);
-            const int in = local - g * (kGroupM * NT);
-            const int mi = first + in % gm;
-            tc.expert = e;
-            tc.mi = in % gm;
-            tc.gm = gm;
-            tc.nt = in / gm;
-            tc.row0 = offsets[e] + mi * BM;
-            tc.rows = min(BM, m_e - mi * BM);
-            return tc;
-        }
-        start += n_tiles;
+        const int local = L - start;
+        const int g = local / (kGroupM * NT);
+        const int head = g * kGroupM;
+        const int gm = min(kGroupM, mt - head);
+        const int in = local - g * (kGroupM * NT);
+        const int mi = head + in % gm;
+        tc.expert = w * kWave + src;
+        tc.mi = in % gm;
+        tc.gm = gm;
+        tc.nt = in / gm;
+        tc.row0 = row_e + mi * BM;
+        tc.rows = min(BM, m_e - mi * BM);
+        return tc;
     }
     return tc;
 }

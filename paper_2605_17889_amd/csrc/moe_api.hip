@@ -22,6 +22,7 @@ struct moe_ctx {
     int32_t* perm;       // [R_max]
     int32_t* inv_perm;   // [R_max]
     int32_t* scratch;    // permutation segment tables
+    float* logits;       // [T_max, E] router logits, only with more than 16 experts (else null)
     moe_bf16* x_perm;    // [R_max, d]
     moe_bf16* H;         // [R_max, f]
     moe_bf16* y_perm;    // [R_max, d]
@@ -40,8 +41,8 @@ using namespace moe;
 bool shape_ok(const moe_shape* s) {
     if (!s) return false;
     if (s->T_max < 0 || s->d_model <= 0 || s->d_ff <= 0 || s->E <= 0 || s->k <= 0) return false;
-    if (s->d_model % 512 != 0 || s->d_ff % 256 != 0) return false;
-    if (s->E > kMaxExperts || s->k > s->E) return false;
+    if (s->d_model % 512 != 0 || s->d_ff % 128 != 0) return false;
+    if (s->E > kMaxExperts || s->k > s->E || s->k > kWave) return false;
     if (static_cast<long long>(s->T_max) * s->k >= (1LL << 31)) return false;
     return true;
 }
@@ -49,7 +50,7 @@ bool shape_ok(const moe_shape* s) {
 size_t align_up(size_t v) { return (v + 255) & ~static_cast<size_t>(255); }
 
 struct Layout {
-    size_t topk_idx, topk_w, counts, offsets, perm, inv_perm, scratch, x_perm, H, y_perm, total;
+    size_t topk_idx, topk_w, counts, offsets, perm, inv_perm, scratch, logits, x_perm, H, y_perm, total;
 };
 
 Layout layout_for(const moe_shape* s) {
@@ -64,6 +65,7 @@ Layout layout_for(const moe_shape* s) {
     L.perm = take(R * 4);
     L.inv_perm = take(R * 4);
     L.scratch = take(permute_scratch_ints(static_cast<int>(R), s->E) * 4);
+    L.logits = take(s->E > 16 ? T * s->E * 4 : 0);
     L.x_perm = take(R * s->d_model * 2);
     L.H = take(R * s->d_ff * 2);
     L.y_perm = take(R * s->d_model * 2);
@@ -99,7 +101,7 @@ int forward_chunk(moe_ctx* c, const moe_bf16* x, const float* w_router, const fl
     const int d = sh.d_model, f = sh.d_ff, E = sh.E, k = sh.k, R = T * k;
     int rc;
     rc = run_stage(c, MOE_STAGE_ROUTE, 1, s, [&] {
-        return launch_route(x, w_router, bias, T, d, E, k, c->topk_idx, c->topk_w, nullptr, s);
+        return launch_route(x, w_router, bias, T, d, E, k, c->topk_idx, c->topk_w, nullptr, c->logits, s);
     });
     if (rc != MOE_OK) return rc;
     rc = run_stage(c, MOE_STAGE_PERMUTE, 3, s, [&] {
@@ -180,6 +182,7 @@ int moe_create(moe_ctx** out, const moe_shape* shape, int device_id) {
     c->perm = reinterpret_cast<int32_t*>(c->base + L.perm);
     c->inv_perm = reinterpret_cast<int32_t*>(c->base + L.inv_perm);
     c->scratch = reinterpret_cast<int32_t*>(c->base + L.scratch);
+    c->logits = shape->E > 16 ? reinterpret_cast<float*>(c->base + L.logits) : nullptr;
     c->x_perm = reinterpret_cast<moe_bf16*>(c->base + L.x_perm);
     c->H = reinterpret_cast<moe_bf16*>(c->base + L.H);
     c->y_perm = reinterpret_cast<moe_bf16*>(c->base + L.y_perm);
@@ -205,7 +208,7 @@ int moe_route(moe_ctx* c, const moe_bf16* x, const float* w_router, const float*
     if (T == 0) return MOE_OK;
     if (!x || !w_router || !topk_idx || !topk_w) return MOE_ERR_INVALID_ARG;
     return launch_route(x, w_router, bias, T, c->shape.d_model, c->shape.E, c->shape.k, topk_idx,
-                        topk_w, logits_out, static_cast<hipStream_t>(stream));
+                        topk_w, logits_out, c->logits, static_cast<hipStream_t>(stream));
 }
 
 int moe_route_from_logits(moe_ctx* c, const float* logits, int32_t T, int32_t* topk_idx,

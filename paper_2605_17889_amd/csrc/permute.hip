@@ -3,8 +3,8 @@
 // per-wavefront histograms, one scan, and an in-wavefront stable rank. Integer only and
 // bit-exact; no atomic operation decides a position.
 //
-// A wavefront owns 256 consecutive ids ("segment"), visited in 4 rounds of 64; lane e keeps the
-// running count of expert e (E <= 64).
+// A wavefront owns 256 consecutive ids ("segment"), visited in 4 rounds of 64; lane l keeps the
+// running counts of experts l, l+64, l+128, l+192 (E <= 256).
 //   1. hist   : seg_hist[g][e] = ids of segment g routed to e          (ballot + popcount)
 //   2. scan   : counts, offsets, and seg_base[g][e] = offsets[e] + sum_{g'<g} seg_hist[g'][e]
 //   3. scatter: position = seg_base[g][e] + rank of the id among equal experts in the segment
@@ -17,8 +17,44 @@ namespace {
 constexpr int kSegIds = 256;                 // ids per wavefront segment
 constexpr int kRounds = kSegIds / kWave;     // 4
 constexpr int kBlockWaves = 4;
+constexpr int kExpertWords = kMaxExperts / kWave;   // experts per lane: 4
 
 __device__ __forceinline__ uint64_t lanemask_lt(int lane) { return (1ull << lane) - 1ull; }
+
+// Lanes of the wavefront that hold the same value as this lane (values in [0, 256), or -1 for
+// "none", which matches nothing): one ballot per bit of the value instead of one per expert.
+__device__ __forceinline__ uint64_t same_value_lanes(int my) {
+    uint64_t m = __ballot(my >= 0);
+#pragma unroll
+    for (int b = 0; b < 8; ++b) {
+        const uint64_t bit = __ballot((my >> b) & 1);
+        m &= ((my >> b) & 1) ? bit : ~bit;
+    }
+    return my >= 0 ? m : 0ull;
+}
+
+// The same histogram for many experts (E > 16): every round finds the lanes that share an
+// expert with 8 ballots, and the first lane of each such set adds the set's size to a
+// wavefront-private table in LDS (one writer per expert and round: no atomics needed).
+__global__ __launch_bounds__(kBlockWaves* kWave) void hist_many_kernel(
+    const int32_t* __restrict__ topk_idx, int R, int E, int32_t* __restrict__ seg_hist) {
+    __shared__ int32_t table[kBlockWaves][kMaxExperts];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wv = threadIdx.x / kWave;
+    const int seg = blockIdx.x * kBlockWaves + wv;
+    const int64_t base = static_cast<int64_t>(seg) * kSegIds;
+    if (base >= R) return;
+    volatile int32_t* cnt = table[wv];      // read and written across lanes: never cached
+    for (int e = lane; e < E; e += kWave) cnt[e] = 0;
+    for (int r = 0; r < kRounds; ++r) {
+        const int64_t i = base + r * kWave + lane;
+        int my = (i < R) ? topk_idx[i] : -1;
+        if (my < 0 || my >= E) my = -1;
+        const uint64_t same = same_value_lanes(my);
+        if (my >= 0 && (same & lanemask_lt(lane)) == 0) cnt[my] += __popcll(same);
+    }
+    for (int e = lane; e < E; e += kWave) seg_hist[static_cast<size_t>(seg) * E + e] = cnt[e];
+}
 
 __global__ __launch_bounds__(kBlockWaves* kWave) void hist_kernel(
     const int32_t* __restrict__ topk_idx, int R, int E, int32_t* __restrict__ seg_hist) {
@@ -26,16 +62,23 @@ __global__ __launch_bounds__(kBlockWaves* kWave) void hist_kernel(
     const int seg = blockIdx.x * kBlockWaves + (threadIdx.x / kWave);
     const int64_t base = static_cast<int64_t>(seg) * kSegIds;
     if (base >= R) return;
-    int cnt = 0;
+    int cnt[kExpertWords] = {0, 0, 0, 0};
     for (int r = 0; r < kRounds; ++r) {
         const int64_t i = base + r * kWave + lane;
         const int my = (i < R) ? topk_idx[i] : -1;
-        for (int e = 0; e < E; ++e) {
-            const uint64_t b = __ballot(my == e);
-            if (lane == e) cnt += __popcll(b);
+#pragma unroll
+        for (int w = 0; w < kExpertWords; ++w) {
+            if (w * kWave >= E) break;
+            const int e_end = min(E - w * kWave, kWave);
+            for (int el = 0; el < e_end; ++el) {
+                const uint64_t b = __ballot(my == w * kWave + el);
+                if (lane == el) cnt[w] += __popcll(b);
+            }
         }
     }
-    if (lane < E) seg_hist[static_cast<size_t>(seg) * E + lane] = cnt;
+#pragma unroll
+    for (int w = 0; w < kExpertWords; ++w)
+        if (w * kWave + lane < E) seg_hist[static_cast<size_t>(seg) * E + w * kWave + lane] = cnt[w];
 }
 
 // One block of 1024 threads (16 wavefronts). Wavefront w scans the columns e = w, w+16, ...
@@ -49,6 +92,7 @@ __global__ __launch_bounds__(1024) void scan_kernel(const int32_t* __restrict__ 
     const int w = threadIdx.x / kWave;
     for (int e = w; e < E; e += 16) {
         int sum = 0;
+#pragma unroll 4
         for (int g = lane; g < nseg; g += kWave) sum += seg_hist[static_cast<size_t>(g) * E + e];
         for (int s = 32; s >= 1; s >>= 1) sum += __shfl_xor(sum, s, kWave);
         if (lane == 0) tot[e] = sum;
@@ -68,16 +112,24 @@ __global__ __launch_bounds__(1024) void scan_kernel(const int32_t* __restrict__ 
     __syncthreads();
     for (int e = w; e < E; e += 16) {
         int carry = off[e];
-        for (int g0 = 0; g0 < nseg; g0 += kWave) {
-            const int g = g0 + lane;
-            const int v = (g < nseg) ? seg_hist[static_cast<size_t>(g) * E + e] : 0;
-            int incl = v;                                  // inclusive prefix over the 64 lanes
-            for (int s = 1; s < kWave; s <<= 1) {
-                const int up = __shfl_up(incl, s, kWave);
-                if (lane >= s) incl += up;
+        for (int g0 = 0; g0 < nseg; g0 += 4 * kWave) {     // four independent loads in flight
+            int v4[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int g = g0 + u * kWave + lane;
+                v4[u] = (g < nseg) ? seg_hist[static_cast<size_t>(g) * E + e] : 0;
             }
-            if (g < nseg) seg_base[static_cast<size_t>(g) * E + e] = carry + incl - v;
-            carry += __shfl(incl, kWave - 1, kWave);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int g = g0 + u * kWave + lane;
+                int incl = v4[u];                          // inclusive prefix over the 64 lanes
+                for (int s = 1; s < kWave; s <<= 1) {
+                    const int up = __shfl_up(incl, s, kWave);
+                    if (lane >= s) incl += up;
+                }
+                if (g < nseg) seg_base[static_cast<size_t>(g) * E + e] = carry + incl - v4[u];
+                carry += __shfl(incl, kWave - 1, kWave);
+            }
         }
     }
 }
@@ -89,17 +141,60 @@ __global__ __launch_bounds__(kBlockWaves* kWave) void scatter_kernel(
     const int seg = blockIdx.x * kBlockWaves + (threadIdx.x / kWave);
     const int64_t base = static_cast<int64_t>(seg) * kSegIds;
     if (base >= R) return;
-    int run = (lane < E) ? seg_base[static_cast<size_t>(seg) * E + lane] : 0;
+    int run[kExpertWords];
+#pragma unroll
+    for (int w = 0; w < kExpertWords; ++w)
+        run[w] = (w * kWave + lane < E) ? seg_base[static_cast<size_t>(seg) * E + w * kWave + lane] : 0;
     for (int r = 0; r < kRounds; ++r) {
         const int64_t i = base + r * kWave + lane;
         const int my = (i < R) ? topk_idx[i] : -1;
         int pos = -1;
-        for (int e = 0; e < E; ++e) {
-            const uint64_t b = __ballot(my == e);
-            const int base_e = __shfl(run, e, kWave);
-            if (my == e) pos = base_e + __popcll(b & lanemask_lt(lane));
-            if (lane == e) run += __popcll(b);
+#pragma unroll
+        for (int w = 0; w < kExpertWords; ++w) {
+            if (w * kWave >= E) break;
+            const int e_end = min(E - w * kWave, kWave);
+            for (int el = 0; el < e_end; ++el) {
+                const int e = w * kWave + el;
+                const uint64_t b = __ballot(my == e);
+                const int base_e = __shfl(run[w], el, kWave);
+                if (my == e) pos = base_e + __popcll(b & lanemask_lt(lane));
+                if (lane == el) run[w] += __popcll(b);
+            }
         }
+        if (i < R) {
+            inv_perm[i] = pos;
+            if (pos >= 0) perm[pos] = static_cast<int32_t>(i);
+        }
+    }
+}
+
+// Scatter for many experts: running positions per expert in a wavefront-private LDS table; the
+// rank of an id inside a round is its position among the lanes with the same expert, and the
+// first of those lanes advances the table (rounds are in id order, so the sort stays stable).
+__global__ __launch_bounds__(kBlockWaves* kWave) void scatter_many_kernel(
+    const int32_t* __restrict__ topk_idx, int R, int E, const int32_t* __restrict__ seg_base,
+    int32_t* __restrict__ perm, int32_t* __restrict__ inv_perm) {
+    __shared__ int32_t table[kBlockWaves][kMaxExperts];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wv = threadIdx.x / kWave;
+    const int seg = blockIdx.x * kBlockWaves + wv;
+    const int64_t base = static_cast<int64_t>(seg) * kSegIds;
+    if (base >= R) return;
+    volatile int32_t* run = table[wv];      // read and written across lanes: never cached
+    for (int e = lane; e < E; e += kWave) run[e] = seg_base[static_cast<size_t>(seg) * E + e];
+    for (int r = 0; r < kRounds; ++r) {
+        const int64_t i = base + r * kWave + lane;
+        int my = (i < R) ? topk_idx[i] : -1;
+        if (my < 0 || my >= E) my = -1;
+        const uint64_t same = same_value_lanes(my);
+        int pos = -1;
+        if (my >= 0) {
+            const int start = run[my];                  // every lane of the set reads first ...
+            pos = start + __popcll(same & lanemask_lt(lane));
+        }
+        // ... then its first lane writes (a wavefront executes the two steps in lockstep, and
+        // LDS operations of one wavefront complete in order)
+        if (my >= 0 && (same & lanemask_lt(lane)) == 0) run[my] = pos + __popcll(same);
         if (i < R) {
             inv_perm[i] = pos;
             if (pos >= 0) perm[pos] = static_cast<int32_t>(i);
@@ -137,14 +232,15 @@ int launch_permute(const int32_t* topk_idx, int R, int E, int32_t* counts, int32
     int32_t* seg_hist = scratch;
     int32_t* seg_base = scratch + static_cast<size_t>(nseg) * E;
     const int blocks = (nseg + kBlockWaves - 1) / kBlockWaves;
+    const bool many = E > 16;            // one ballot per expert below, 9 per round above
     if (nseg > 0)
-        hipLaunchKernelGGL(hist_kernel, dim3(blocks), dim3(kBlockWaves * kWave), 0, s, topk_idx, R,
-                           E, seg_hist);
+        hipLaunchKernelGGL(many ? hist_many_kernel : hist_kernel, dim3(blocks),
+                           dim3(kBlockWaves * kWave), 0, s, topk_idx, R, E, seg_hist);
     hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(1024), 0, s, seg_hist, nseg, E, counts, offsets,
                        seg_base);
     if (nseg > 0)
-        hipLaunchKernelGGL(scatter_kernel, dim3(blocks), dim3(kBlockWaves * kWave), 0, s, topk_idx,
-                           R, E, seg_base, perm, inv_perm);
+        hipLaunchKernelGGL(many ? scatter_many_kernel : scatter_kernel, dim3(blocks),
+                           dim3(kBlockWaves * kWave), 0, s, topk_idx, R, E, seg_base, perm, inv_perm);
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
 

@@ -9,10 +9,44 @@
 // each (token, expert) accumulator sees exactly that order.
 //
 // HBM traffic per token: 2*d_model bytes of x read, 8*k bytes written.
+#include <type_traits>
+
 #include "common.h"
 
 namespace moe {
 namespace {
+
+// Sum of N per-lane values over the 64 lanes in the order of the xor butterfly (partner
+// distances 32, 16, ..., 1), without keeping every sum in every lane: while more than one value
+// is left, the two partners split them (the lane with the distance bit clear keeps the lower
+// half) and each adds its partner's half, so a step moves half as many values as the one
+// before. a + b == b + a bitwise, hence v[0] of lane l equals what the full butterfly would
+// leave everywhere for value l >> (6 - log2 N). N - 1 + (6 - log2 N) shuffles instead of 6N.
+template <int N, int LEFT, int S>
+__device__ __forceinline__ void halving_step(float (&v)[N], int lane) {
+    if constexpr (S >= 1) {
+        if constexpr (LEFT > 1) {
+            constexpr int H = LEFT / 2;
+            const bool upper = (lane & S) != 0;
+#pragma unroll
+            for (int n = 0; n < H; ++n) {
+                const float send = upper ? v[n] : v[n + H];
+                const float keep = upper ? v[n + H] : v[n];
+                v[n] = keep + __shfl_xor(send, S, kWave);
+            }
+            halving_step<N, H, S / 2>(v, lane);
+        } else {
+            v[0] = v[0] + __shfl_xor(v[0], S, kWave);
+            halving_step<N, 1, S / 2>(v, lane);
+        }
+    }
+}
+template <int N>
+__device__ __forceinline__ void halving_reduce(float (&v)[N], int lane) {
+    static_assert(N >= 1 && N <= kWave && (N & (N - 1)) == 0, "power of two up to 64");
+    halving_step<N, N, 32>(v, lane);
+}
+
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -47,6 +81,7 @@ __device__ __forceinline__ void select_and_gate(const float (&l)[EP], int E, int
     for (int s = 0; s < k; ++s) w_out[s] = w_out[s] / den;
 }
 
+// Up to 16 experts, any count: W_r is read from global memory (L2) by every wavefront.
 template <int EP, int TOK>
 __global__ __launch_bounds__(256) void route_kernel(const uint16_t* __restrict__ x,
                                                     const float* __restrict__ wr,
@@ -122,6 +157,58 @@ __global__ __launch_bounds__(256) void route_kernel(const uint16_t* __restrict__
     }
 }
 
+// Selection and gates for more than 64 experts: one wavefront per token, lane l holds the
+// logits of experts l, l+64, l+128, l+192. Each of the k rounds takes the largest remaining
+// logit of the wavefront (ties -> lower expert index, NaN below every number) by a butterfly
+// of (value, index) pairs; the gates are the softmax over the selected logits, accumulated in
+// slot order like select_and_gate().
+__global__ __launch_bounds__(256) void route_select_kernel(const float* __restrict__ logits, int T,
+                                                           int E, int k,
+                                                           int32_t* __restrict__ topk_idx,
+                                                           float* __restrict__ topk_w) {
+    constexpr int EW = kMaxExperts / kWave;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int t = (blockIdx.x * blockDim.x + threadIdx.x) / kWave;
+    if (t >= T) return;
+    float v[EW];
+#pragma unroll
+    for (int w = 0; w < EW; ++w) {
+        const int e = w * kWave + lane;
+        float l = (e < E) ? logits[static_cast<size_t>(t) * E + e] : -INFINITY;
+        v[w] = (l != l) ? -INFINITY : l;
+    }
+    unsigned taken = 0;                                   // bit w: expert w*64+lane is selected
+    float top = 0.f, den = 0.f, my_w = 0.f;              // lane s keeps the weight of slot s
+    int my_idx = 0;
+    for (int s = 0; s < k; ++s) {
+        // best of this lane: ascending expert index, strict '>' keeps the lower index on ties
+        float bv = 0.f;
+        int be = -1;
+#pragma unroll
+        for (int w = 0; w < EW; ++w) {
+            const int e = w * kWave + lane;
+            if (e < E && !((taken >> w) & 1u) && (be < 0 || v[w] > bv)) { bv = v[w]; be = e; }
+        }
+        // best of the wavefront: larger value, then lower index; lanes without a candidate lose
+#pragma unroll
+        for (int m = 32; m >= 1; m >>= 1) {
+            const float ov = __shfl_xor(bv, m, kWave);
+            const int oe = __shfl_xor(be, m, kWave);
+            const bool other = oe >= 0 && (be < 0 || ov > bv || (ov == bv && oe < be));
+            if (other) { bv = ov; be = oe; }
+        }
+        if ((be & (kWave - 1)) == lane) taken |= 1u << (be >> 6);   // be >= 0 because k <= E
+        if (s == 0) top = bv;
+        const float w = expf(bv - top);
+        den += w;
+        if (lane == s) { my_w = w; my_idx = be; }             // k <= 64: one slot per lane
+    }
+    if (lane < k) {
+        topk_idx[static_cast<size_t>(t) * k + lane] = my_idx;
+        topk_w[static_cast<size_t>(t) * k + lane] = my_w / den;
+    }
+}
+
 // Fast path for E in {8, 16}: the same arithmetic, but the 512 x E slice of W_r that a chunk
 // needs is staged once per workgroup in LDS (coalesced 16-byte global reads) and every lane
 // then pulls its own 8 x E weights with 16-byte LDS reads. Lane l's 8*E floats sit at byte
@@ -165,39 +252,60 @@ __global__ __launch_bounds__(256) void route_kernel_lds(const uint16_t* __restri
             *reinterpret_cast<u32x4*>(&wlds[buf][l * LANE_BYTES + within]) = stage[i];
         }
     };
-    load_w(0);
-    store_w(0);
-    __syncthreads();
-    for (int j = 0; j < chunks; ++j) {
-        const int buf = j & 1;
-        if (j + 1 < chunks) load_w(j + 1);
-        const int i0 = 512 * j + 8 * lane;
-        u32x4 xv[TOK];
+    u32x4 xnext[TOK];
+    auto load_x = [&](int j) {
 #pragma unroll
         for (int q = 0; q < TOK; ++q) {
             const int t = min(t0 + q, T - 1);   // clamp: the duplicate result is never stored
-            xv[q] = *reinterpret_cast<const u32x4*>(x + static_cast<size_t>(t) * d + i0);
+            xnext[q] = *reinterpret_cast<const u32x4*>(x + static_cast<size_t>(t) * d + 512 * j +
+                                                       8 * lane);
+        }
+    };
+    load_w(0);
+    load_x(0);
+    store_w(0);
+    __syncthreads();
+    // One chunk; MORE is a compile-time flag (last chunk: nothing further to fetch) so that the
+    // steady loop has no branch for the compiler to move the multiply-adds across.
+    auto chunk = [&](int j, auto more) {
+        constexpr bool MORE = decltype(more)::value;
+        const int buf = j & 1;
+        u32x4 xv[TOK];
+#pragma unroll
+        for (int q = 0; q < TOK; ++q) xv[q] = xnext[q];
+        if constexpr (MORE) {                   // the next chunk's operands fly during this one
+            load_w(j + 1);
+            load_x(j + 1);
         }
         const unsigned char* mine = &wlds[buf][lane * LANE_BYTES];
+        // Rows are read one ahead of the multiply-adds that use them; the fences keep the
+        // compiler from hoisting all eight rows' reads (128 registers) to the top.
+        f32x4 wrow[2][E / 4];
+#pragma unroll
+        for (int c = 0; c < E / 4; ++c) wrow[0][c] = *reinterpret_cast<const f32x4*>(mine + c * 16);
 #pragma unroll
         for (int v = 0; v < 8; ++v) {
-            float w[E];
+            if (v + 1 < 8) {
 #pragma unroll
-            for (int c = 0; c < E / 4; ++c) {
-                const f32x4 f = *reinterpret_cast<const f32x4*>(mine + (v * E + c * 4) * 4);
-                w[c * 4 + 0] = f[0]; w[c * 4 + 1] = f[1]; w[c * 4 + 2] = f[2]; w[c * 4 + 3] = f[3];
+                for (int c = 0; c < E / 4; ++c)
+                    wrow[(v + 1) & 1][c] =
+                        *reinterpret_cast<const f32x4*>(mine + ((v + 1) * E + c * 4) * 4);
             }
 #pragma unroll
             for (int q = 0; q < TOK; ++q) {
                 const uint32_t word = xv[q][v >> 1];
                 const float xf = __uint_as_float((v & 1) ? (word & 0xffff0000u) : (word << 16));
 #pragma unroll
-                for (int e = 0; e < E; ++e) acc[q][e] = fmaf(xf, w[e], acc[q][e]);
+                for (int e = 0; e < E; ++e)
+                    acc[q][e] = fmaf(xf, wrow[v & 1][e >> 2][e & 3], acc[q][e]);
             }
+            __builtin_amdgcn_sched_barrier(0);
         }
-        if (j + 1 < chunks) store_w(buf ^ 1);
+        if constexpr (MORE) store_w(buf ^ 1);
         __syncthreads();
-    }
+    };
+    for (int j = 0; j + 1 < chunks; ++j) chunk(j, std::true_type{});
+    chunk(chunks - 1, std::false_type{});
 
 #pragma unroll
     for (int s = 32; s >= 1; s >>= 1)
@@ -226,6 +334,119 @@ __global__ __launch_bounds__(256) void route_kernel_lds(const uint16_t* __restri
                                topk_w + static_cast<size_t>(t) * k);
         }
     }
+}
+
+// Logits for more than 16 experts: the experts are cut into groups of 16, one workgroup takes
+// 4*TOK tokens and one group, and stages that group's 512 x 16 slice of W_r per chunk in LDS
+// exactly like route_kernel_lds (rows of W_r are E floats apart here). Every (token, expert)
+// accumulator still sees the canonical order. Only the logits are stored; the selection runs
+// afterwards (route_from_logits_kernel or route_select_kernel).
+template <int TOK, bool VEC>
+__global__ __launch_bounds__(256, 2) void route_logits_group_kernel(const uint16_t* __restrict__ x,
+                                                                 const float* __restrict__ wr,
+                                                                 const float* __restrict__ bias,
+                                                                 int T, int d, int E,
+                                                                 float* __restrict__ logits_out) {
+    constexpr int EG = 16;                              // experts per group
+    constexpr int LANE_BYTES = 32 * EG + 16;            // padded per-lane slice (8 rows x 16 floats)
+    constexpr int VEC_PER_THREAD = 512 * EG * 4 / 16 / 256;   // 8
+    __shared__ __attribute__((aligned(16))) unsigned char wlds[2][64 * LANE_BYTES];
+
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave_in_block = threadIdx.x / kWave;
+    const int t0 = (blockIdx.x * 4 + wave_in_block) * TOK;
+    const int e0 = blockIdx.y * EG;
+
+    float acc[TOK * EG];                                // [token][expert of the group]
+#pragma unroll
+    for (int n = 0; n < TOK * EG; ++n) acc[n] = 0.f;
+
+    const int chunks = d / 512;
+    f32x4 stage[VEC_PER_THREAD];
+    auto load_w = [&](int j) {
+#pragma unroll
+        for (int i = 0; i < VEC_PER_THREAD; ++i) {
+            const int vi = threadIdx.x + i * 256;        // vector index inside the 512 x 16 slice
+            const int r = vi >> 2, c4 = (vi & 3) * 4;
+            const float* src = wr + static_cast<size_t>(512 * j + r) * E + e0 + c4;
+            if (VEC) {                                    // 16-byte loads aligned and inside
+                stage[i] = *reinterpret_cast<const f32x4*>(src);
+            } else {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) stage[i][c] = (e0 + c4 + c < E) ? src[c] : 0.f;
+            }
+        }
+    };
+    auto store_w = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < VEC_PER_THREAD; ++i) {
+            const int vi = threadIdx.x + i * 256;
+            const int r = vi >> 2, c4 = (vi & 3) * 4;
+            *reinterpret_cast<f32x4*>(&wlds[buf][(r >> 3) * LANE_BYTES + ((r & 7) * EG + c4) * 4]) = stage[i];
+        }
+    };
+    u32x4 xnext[TOK];
+    auto load_x = [&](int j) {
+#pragma unroll
+        for (int q = 0; q < TOK; ++q) {
+            const int t = min(t0 + q, T - 1);   // clamp: the duplicate result is never stored
+            xnext[q] = *reinterpret_cast<const u32x4*>(x + static_cast<size_t>(t) * d + 512 * j +
+                                                       8 * lane);
+        }
+    };
+    load_w(0);
+    load_x(0);
+    store_w(0);
+    __syncthreads();
+    // One chunk; MORE is a compile-time flag (last chunk: nothing further to fetch) so that the
+    // steady loop has no branch for the compiler to move the multiply-adds across.
+    auto chunk = [&](int j, auto more) {
+        constexpr bool MORE = decltype(more)::value;
+        const int buf = j & 1;
+        u32x4 xv[TOK];
+#pragma unroll
+        for (int q = 0; q < TOK; ++q) xv[q] = xnext[q];
+        if constexpr (MORE) {                   // the next chunk's operands fly during this one
+            load_w(j + 1);
+            load_x(j + 1);
+        }
+        const unsigned char* mine = &wlds[buf][lane * LANE_BYTES];
+        // Rows are read one ahead of the multiply-adds that use them; the fences keep the
+        // compiler from hoisting all eight rows' reads (128 registers) to the top.
+        f32x4 wrow[2][EG / 4];
+#pragma unroll
+        for (int c = 0; c < EG / 4; ++c) wrow[0][c] = *reinterpret_cast<const f32x4*>(mine + c * 16);
+#pragma unroll
+        for (int v = 0; v < 8; ++v) {
+            if (v + 1 < 8) {
+#pragma unroll
+                for (int c = 0; c < EG / 4; ++c)
+                    wrow[(v + 1) & 1][c] =
+                        *reinterpret_cast<const f32x4*>(mine + ((v + 1) * EG + c * 4) * 4);
+            }
+#pragma unroll
+            for (int q = 0; q < TOK; ++q) {
+                const uint32_t word = xv[q][v >> 1];
+                const float xf = __uint_as_float((v & 1) ? (word & 0xffff0000u) : (word << 16));
+#pragma unroll
+                for (int e = 0; e < EG; ++e)
+                    acc[q * EG + e] = fmaf(xf, wrow[v & 1][e >> 2][e & 3], acc[q * EG + e]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if constexpr (MORE) store_w(buf ^ 1);
+        __syncthreads();
+    };
+    for (int j = 0; j + 1 < chunks; ++j) chunk(j, std::true_type{});
+    chunk(chunks - 1, std::false_type{});
+
+    // Lane 16*q + e ends with the logit of token t0+q and expert e0+e.
+    halving_reduce<TOK * EG>(acc, lane);
+    static_assert(TOK * EG == kWave, "one result per lane");
+    const int q = lane / EG, e = lane % EG, t = t0 + q;
+    if (t < T && e0 + e < E)
+        logits_out[static_cast<size_t>(t) * E + e0 + e] =
+            bias != nullptr ? acc[0] + bias[e0 + e] : acc[0];
 }
 
 template <int E_, int TOK>
@@ -262,22 +483,46 @@ int launch_route_t(const moe_bf16* x, const float* wr, const float* bias, int T,
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
 
+int launch_select_wave(const float* logits, int T, int E, int k, int32_t* idx, float* w,
+                       hipStream_t s) {
+    const int blocks = (T + 3) / 4;                       // 4 wavefronts = 4 tokens per block
+    hipLaunchKernelGGL(route_select_kernel, dim3(blocks), dim3(256), 0, s, logits, T, E, k, idx, w);
+    return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
+}
+
 }  // namespace
 
+// `logits_scratch` [T, E] fp32 is only used for more than 16 experts, and only if the caller
+// does not ask for the logits anyway.
 int launch_route(const moe_bf16* x, const float* w_router, const float* bias, int T, int d, int E,
-                 int k, int32_t* topk_idx, float* topk_w, float* logits_out, hipStream_t s) {
+                 int k, int32_t* topk_idx, float* topk_w, float* logits_out,
+                 float* logits_scratch, hipStream_t s) {
     if (T == 0) return MOE_OK;
+    if (E > 16) {
+        // logits by expert groups of 16 with W_r staged in LDS, then the selection
+        float* logits = logits_out ? logits_out : logits_scratch;
+        if (!logits) return MOE_ERR_INVALID_ARG;
+        constexpr int TOK = 4;
+        const dim3 grid((T + 4 * TOK - 1) / (4 * TOK), (E + 15) / 16);
+        if (E % 16 == 0)     // every group full and 16-byte aligned: vector loads of W_r
+            hipLaunchKernelGGL((route_logits_group_kernel<TOK, true>), grid, dim3(256), 0, s, x,
+                               w_router, bias, T, d, E, logits);
+        else
+            hipLaunchKernelGGL((route_logits_group_kernel<TOK, false>), grid, dim3(256), 0, s, x,
+                               w_router, bias, T, d, E, logits);
+        if (hipGetLastError() != hipSuccess) return MOE_ERR_HIP;
+        return launch_route_from_logits(logits, T, E, k, topk_idx, topk_w, s);
+    }
     if (E == 8) return launch_route_lds<8, 2>(x, w_router, bias, T, d, k, topk_idx, topk_w, logits_out, s);
     if (E == 16) return launch_route_lds<16, 2>(x, w_router, bias, T, d, k, topk_idx, topk_w, logits_out, s);
     if (E <= 8) return launch_route_t<8, 4>(x, w_router, bias, T, d, E, k, topk_idx, topk_w, logits_out, s);
-    if (E <= 16) return launch_route_t<16, 2>(x, w_router, bias, T, d, E, k, topk_idx, topk_w, logits_out, s);
-    if (E <= 32) return launch_route_t<32, 1>(x, w_router, bias, T, d, E, k, topk_idx, topk_w, logits_out, s);
-    return launch_route_t<64, 1>(x, w_router, bias, T, d, E, k, topk_idx, topk_w, logits_out, s);
+    return launch_route_t<16, 2>(x, w_router, bias, T, d, E, k, topk_idx, topk_w, logits_out, s);
 }
 
 int launch_route_from_logits(const float* logits, int T, int E, int k, int32_t* topk_idx,
                              float* topk_w, hipStream_t s) {
     if (T == 0) return MOE_OK;
+    if (E > 64) return launch_select_wave(logits, T, E, k, topk_idx, topk_w, s);
     const int blocks = (T + 255) / 256;
 #define MOE_RFL(EP)                                                                              \
     hipLaunchKernelGGL((route_from_logits_kernel<EP>), dim3(blocks), dim3(256), 0, s, logits, T, \

@@ -6,7 +6,7 @@ HIP path's tests/bench consume the same bytes produced here.
 
 Shapes follow the five benchmark configurations: a Tiny layer, a Mixtral-8x7B-shaped
 batched decode step, a Mixtral-8x22B-shaped prefill chunk, the coalesced-vs-micro-batched
-comparison, and the Zipf(1.2)-skewed routing case. The paper's own workloads are real
+comparison, and the Zipf(1.2)-skewed routing case; two more presets have many small experts. The paper's own workloads are real
 checkpoints (Mixtral-8x7B-Instruct, DeepSeek-V2-Lite, Qwen3-30B-A3B; Section 6.1) and a
 BIG-Bench-Hard expert-load histogram (Fig. 3(c)); none of those are available, so these
 random layers of the same shape and a Zipf-shaped expert load stand in for them.
@@ -54,6 +54,14 @@ PRESETS: Dict[str, LayerConfig] = {
                                      zipf_s=1.2),
     "mixtral8x22b_zipf_empty": LayerConfig("mixtral8x22b_zipf_empty", 16384, 6144, 16384, 8, 2,
                                            seed=5, zipf_s=1.2, empty_expert=True),
+    # Layers with numerous smaller experts, shaped like the paper's other two models
+    # (Section 6.1). The paper prints no dimensions; these are the public model cards' values:
+    # Qwen3-30B-A3B: hidden 2048, expert dim 768, 128 experts, top-8; DeepSeek-V2-Lite: hidden
+    # 2048, expert dim 1408, 64 routed experts, top-6 (its two always-on shared experts are a
+    # plain dense FFN and not part of the routed path).
+    "qwen3_30b_a3b_prefill": LayerConfig("qwen3_30b_a3b_prefill", 8192, 2048, 768, 128, 8, seed=6),
+    "deepseek_v2_lite_prefill": LayerConfig("deepseek_v2_lite_prefill", 8192, 2048, 1408, 64, 6,
+                                            seed=7),
 }
 
 

@@ -61,14 +61,18 @@ def test_workspace_bytes_and_shape_rules(lib):
     assert n >= R * (6144 * 2 * 2 + 16384 * 2)            # x_perm + y_perm + H
     assert n < R * (6144 * 2 * 2 + 16384 * 2) + (8 << 20)
     for bad in (MoeShape(16, 500, 1024, 8, 2),             # d_model % 512
-                MoeShape(16, 512, 1000, 8, 2),             # d_ff % 256
-                MoeShape(16, 512, 1024, 65, 2),            # E > 64
+                MoeShape(16, 512, 1000, 8, 2),             # d_ff % 128
+                MoeShape(16, 512, 1024, 257, 2),           # E > 256
+                MoeShape(16, 512, 1024, 128, 65),          # k > 64
                 MoeShape(16, 512, 1024, 4, 5),             # k > E
                 MoeShape(16, 512, 1024, 8, 0),             # k < 1
                 MoeShape(-1, 512, 1024, 8, 2),
                 MoeShape(1 << 30, 512, 1024, 8, 2)):       # T_max*k >= 2^31
         assert lib.moe_workspace_bytes(C.byref(bad)) == 0
     assert lib.moe_workspace_bytes(None) == 0
+    for good in (MoeShape(16, 2048, 768, 128, 8), MoeShape(16, 2048, 1408, 64, 6),
+                 MoeShape(16, 512, 128, 256, 64)):
+        assert lib.moe_workspace_bytes(C.byref(good)) > 0
 
 
 def test_null_arguments_are_rejected_before_any_gpu_work(lib):

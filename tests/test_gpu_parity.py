@@ -68,6 +68,9 @@ def rand_bits(rng, shape, std):
     (1, 512, 8, 2, False), (3, 512, 8, 2, True), (257, 1024, 8, 2, False), (130, 512, 5, 3, True),
     (64, 512, 16, 4, False), (33, 512, 33, 6, True), (70, 512, 64, 8, True), (19, 1536, 8, 8, False),
     (5, 512, 1, 1, False),
+    # more than 64 experts: logits in passes of 64 experts, selection by one wavefront per token
+    (70, 2048, 128, 8, True), (33, 512, 65, 3, False), (21, 1024, 200, 10, True),
+    (9, 512, 256, 64, False), (130, 512, 129, 1, True),
 ])
 def test_route_bit_exact(T, d, E, k, use_bias):
     say(f"route T={T} d={d} E={E} k={k} bias={use_bias}")
@@ -139,10 +142,42 @@ def test_route_from_logits_golden_ties():
         ctx.close()
 
 
+def test_route_from_logits_many_experts_ties_and_order():
+    """More than 64 experts (wavefront selection): ties go to the lower index across lanes and
+    across the 64-expert words, -0.0 == +0.0, NaN ranks last, slots are in descending order."""
+    E, k = 200, 6
+    lg = np.full((4, E), -1.0, np.float32)
+    lg[0, [199, 70, 6, 134]] = 2.0                       # four equal maxima: 6, 70, 134, 199
+    lg[0, 65] = 1.5
+    lg[0, 1] = 1.0
+    lg[1, :] = 0.0                                       # all equal: experts 0..5
+    lg[1, 3] = -0.0
+    lg[2, :] = np.nan                                    # NaN everywhere except three
+    lg[2, [190, 64, 63]] = [-5.0, -7.0, -6.0]
+    lg[3, :] = np.linspace(-3, 3, E).astype(np.float32)  # strictly increasing: 199, 198, ...
+    want = [[6, 70, 134, 199, 65, 1], [0, 1, 2, 3, 4, 5], [190, 63, 64, 0, 1, 2],
+            [199, 198, 197, 196, 195, 194]]
+    ctx = B.MoeContext(4, 512, 256, E, k)
+    idx = torch.empty((4, k), dtype=torch.int32, device="cuda")
+    g = torch.empty((4, k), dtype=torch.float32, device="cuda")
+    B.moe_route_from_logits(ctx, dev(lg), 4, idx, g)
+    torch.cuda.synchronize()
+    assert idx.cpu().numpy().tolist() == want
+    gh = g.cpu().numpy()
+    assert np.allclose(gh[1], 1.0 / k, atol=GATE_TOL)
+    e = np.exp(np.array([0, 0, 0, 0, -0.5, -1.0]))
+    assert np.allclose(gh[0], e / e.sum(), atol=GATE_TOL)
+    idx_ref, g_ref = ref.topk(lg[[0, 1, 3]], k)
+    assert np.array_equal(idx.cpu().numpy()[[0, 1, 3]], idx_ref)
+    assert np.max(np.abs(gh[[0, 1, 3]] - g_ref)) <= GATE_TOL
+    ctx.close()
+
+
 # --------------------------------------------------------------------------- permutation
 @pytest.mark.parametrize("T,E,k,seed,empty", [
     (1, 8, 2, 0, False), (37, 8, 2, 1, True), (256, 8, 2, 2, False), (1000, 64, 6, 3, False),
     (4096, 8, 2, 4, True), (777, 3, 3, 5, False), (16384, 8, 2, 6, False), (129, 40, 1, 7, True),
+    (5000, 128, 8, 8, True), (333, 65, 2, 9, False), (2000, 256, 6, 10, True), (64, 200, 64, 11, False),
 ])
 def test_permute_bit_exact(T, E, k, seed, empty):
     say(f"permute T={T} E={E} k={k} empty={empty}")
@@ -457,6 +492,9 @@ def test_layer_mixtral8x22b_zipf(experts_8x22b, preset):
     (257, 1024, 512, 16, 4, False),
     (40, 512, 256, 3, 3, True),        # k = E: every token visits every expert
     (129, 512, 768, 5, 1, False),      # top-1
+    (700, 2048, 768, 128, 8, True),    # Qwen3-30B-A3B-shaped: 128 small experts, top-8
+    (300, 2048, 1408, 64, 6, False),   # DeepSeek-V2-Lite-shaped: expert dim not a multiple of 256
+    (500, 512, 128, 256, 5, True),     # the most experts and the smallest expert dim supported
 ])
 def test_layer_other_expert_shapes(T, d, f, E, k, use_bias):
     say(f"layer T={T} d={d} f={f} E={E} k={k}")
