@@ -134,10 +134,12 @@ def main():
     ap.add_argument("--workload", default="mixtral8x22b_prefill")
     ap.add_argument("--micro", type=int, default=0,
                     help="run the micro-batched call with this many tokens per micro-batch")
+    ap.add_argument("--tokens", type=int, default=0,
+                    help="override the preset's token count T (same layer shape and routing recipe)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--gemm-config", type=int, default=-1,
-                    help="force the expert-GEMM tile configuration (0 large, 1 medium, 2 small); "
-                         "-1 = automatic")
+                    help="force the expert-GEMM tile configuration (0 large, 1 medium, 2 small, "
+                         "3 tiny; +16 cached / +32 non-temporal weight loads); -1 = automatic")
     ap.add_argument("--planner-sweep", action="store_true",
                     help="run the workload coalesced and as micro-batches of 64..T/2 tokens and "
                          "print, per micro-batch size, the measured expert-GEMM time next to the "
@@ -168,6 +170,9 @@ def main():
                                                "launches": 10}}), flush=True)
         return
     cfg = synth.PRESETS[args.workload]
+    if args.tokens > 0:
+        import dataclasses
+        cfg = dataclasses.replace(cfg, T=args.tokens)
     T = cfg.T
     B.moe_set_gemm_config(args.gemm_config)
     log(f"[bench] generating {cfg.name}: T={T} d={cfg.d_model} f={cfg.d_ff} E={cfg.E} k={cfg.k}")

@@ -193,9 +193,12 @@ int moe_estimate_expert_stage(const moe_shape* shape, const int32_t* rows, int32
                               const moe_machine* machine, moe_expert_estimate* out);
 
 /* Tuning / testing knob, process-wide: force the expert-GEMM tile configuration
- * (0 = large, 1 = medium, 2 = small rows-per-expert tile) or -1 for the automatic choice by
- * average rows per expert. Every configuration produces identical bits (same accumulation
- * chain per output element); only speed differs. Returns MOE_ERR_INVALID_ARG otherwise. */
+ * (0 = large, 1 = medium, 2 = small, 3 = tiny rows-per-expert tile) or -1 for the automatic choice by
+ * average rows per expert. Adding 16 to any of these makes the medium and small tiles load the
+ * weights as ordinary (cached) lines, adding 32 as non-temporal ones; without either the library
+ * picks non-temporal loads when about every expert has a single row tile (decode), where each
+ * weight byte is used once. Every setting produces identical bits (same accumulation chain per
+ * output element); only speed differs. Returns MOE_ERR_INVALID_ARG for other values. */
 int moe_set_gemm_config(int config);
 
 #ifdef __cplusplus

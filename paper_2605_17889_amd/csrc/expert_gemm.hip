@@ -58,24 +58,34 @@ int launch_grouped(const moe_bf16* A, const moe_bf16* B0, const moe_bf16* B1, mo
 
 // Tile configuration by average rows per expert. All configurations give identical bits.
 int g_forced_config = -1;   // -1: automatic; 0,1,2: force (tests / tuning)
+int g_stream_mode = -1;     // -1: automatic; 0: weights never non-temporal; 1: always (medium/small)
 
 int pick_config(int R, int E) {
     if (g_forced_config >= 0) return g_forced_config;
-    // 0: pipelined 256x256 tiles. 1: 128-row tiles (generic kernel). 2: a few rows per expert
-    // (64-row tiles). Between 0 and 1 the padded rows decide: groups a little above a multiple
+    // 0: pipelined 256x256 tiles. 1: 128-row tiles (generic kernel). 2: a few dozen rows per
+    // expert (64-row tiles). 3: a handful (32-row tiles, deep weight ring). Between 0 and 1 the padded rows decide: groups a little above a multiple
     // of 256 rows waste most of a large tile. Per-expert counts are not known on the host, so
     // the choice prices the average group plus two standard deviations of a uniform routing,
     // and the large tiles at 0.8 of the time per padded row of the 128-row ones (measured on
     // micro-batches of 64 to 4096 tokens at the 8x22B shape).
     const double avg = static_cast<double>(R) / (E > 0 ? E : 1);
-    if (avg <= 32.0) return 2;
     const double upper = avg + 2.0 * std::sqrt(avg);
+    if (upper <= 32.0) return 3;
+    if (avg <= 32.0) return 2;
     const double padded_large = std::ceil(upper / 256.0) * 256.0;
     const double padded_mid = std::ceil(upper / 128.0) * 128.0;
     return padded_large * 0.8 <= padded_mid ? 0 : 1;
 }
 
-//                      BM   BN  BK WM WN NSTAGE DUAL
+// Weights may be loaded as non-temporal when (almost) every expert has a single m-tile: then no
+// other tile asks for the same weight bytes and keeping them cached only displaces the rows.
+bool single_m_tile(int R, int E, int BM) {
+    if (g_stream_mode >= 0) return g_stream_mode != 0;
+    const double avg = static_cast<double>(R) / (E > 0 ? E : 1);
+    return avg + 2.0 * std::sqrt(avg) <= BM;
+}
+
+//                      BM   BN  BK WM WN NSTAGE DUAL [STREAM_B]
 using GateUpLarge = Config<256, 256, 64, 2, 4, 2, true>;
 using GateUpMid   = Config<128, 256, 64, 2, 4, 3, true>;
 using GateUpSmall = Config<64, 128, 64, 1, 2, 4, true>;
@@ -83,10 +93,23 @@ using DownLarge   = Config<256, 256, 64, 2, 4, 2, false>;
 using DownMid     = Config<128, 128, 64, 2, 2, 4, false>;
 using DownMidWide = Config<128, 256, 64, 2, 4, 3, false>;
 using DownSmall   = Config<64, 64, 64, 1, 2, 4, false>;
+using GateUpMidS   = Config<128, 256, 64, 2, 4, 3, true, true>;
+using GateUpSmallS = Config<64, 128, 64, 1, 2, 4, true, true>;
+using DownMidS     = Config<128, 128, 64, 2, 2, 4, false, true>;
+using DownMidWideS = Config<128, 256, 64, 2, 4, 3, false, true>;
+using DownSmallS   = Config<64, 64, 64, 1, 2, 4, false, true>;
+// a handful of rows per expert (decode): 32-row tiles leave LDS for seven 16 KB weight stages
+using GateUpTiny   = Config<32, 128, 64, 1, 2, 7, true>;
+using GateUpTinyS  = Config<32, 128, 64, 1, 2, 7, true, true>;
+using DownTiny     = Config<32, 128, 64, 1, 2, 7, false>;
+using DownTinyS    = Config<32, 128, 64, 1, 2, 7, false, true>;
 
 }  // namespace
 
-void set_gemm_config(int cfg) { g_forced_config = cfg; }
+void set_gemm_config(int cfg, int stream_mode) {
+    g_forced_config = cfg;
+    g_stream_mode = stream_mode;
+}
 
 // `a` is the grouped activation matrix [R, d] when row_index is NULL; otherwise it is the
 // token matrix [T, d] and grouped row p reads token row_index[p] / index_div (the caller makes
@@ -100,8 +123,18 @@ int launch_gateup(const moe_bf16* a, const int32_t* row_index, int index_div,
     if (config == 0 && d / 64 < 3) config = 1;     // the pipelined kernel needs three k-steps
     switch (config) {
         case 0: return launch_grouped<GateUpLarge, 2, 3>(x_perm, W1, W3, H, offsets, row_index, index_div, R, E, f, d, s);
-        case 1: return launch_grouped<GateUpMid>(x_perm, W1, W3, H, offsets, row_index, index_div, R, E, f, d, s);
-        default: return launch_grouped<GateUpSmall>(x_perm, W1, W3, H, offsets, row_index, index_div, R, E, f, d, s);
+        case 1:
+            if (single_m_tile(R, E, 128))
+                return launch_grouped<GateUpMidS>(x_perm, W1, W3, H, offsets, row_index, index_div, R, E, f, d, s);
+            return launch_grouped<GateUpMid>(x_perm, W1, W3, H, offsets, row_index, index_div, R, E, f, d, s);
+        case 3:
+            if (single_m_tile(R, E, 32))
+                return launch_grouped<GateUpTinyS>(x_perm, W1, W3, H, offsets, row_index, index_div, R, E, f, d, s);
+            return launch_grouped<GateUpTiny>(x_perm, W1, W3, H, offsets, row_index, index_div, R, E, f, d, s);
+        default:
+            if (single_m_tile(R, E, 64))
+                return launch_grouped<GateUpSmallS>(x_perm, W1, W3, H, offsets, row_index, index_div, R, E, f, d, s);
+            return launch_grouped<GateUpSmall>(x_perm, W1, W3, H, offsets, row_index, index_div, R, E, f, d, s);
     }
 }
 
@@ -115,10 +148,25 @@ int launch_down(const moe_bf16* H, const int32_t* offsets, int R, int d, int f, 
         case 1:
             // HBM-bound: wide tiles stream more bytes per workgroup, but only if there are
             // enough of them to occupy the 256 compute units (about one m-tile per expert).
-            if (static_cast<long long>(E) * (d / 256) >= 160 && d % 256 == 0)
+            if (static_cast<long long>(E) * (d / 256) >= 160 && d % 256 == 0) {
+                if (single_m_tile(R, E, 128))
+                    return launch_grouped<DownMidWideS>(H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
                 return launch_grouped<DownMidWide>(H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
+            }
+            if (single_m_tile(R, E, 128))
+                return launch_grouped<DownMidS>(H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
             return launch_grouped<DownMid>(H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
-        default: return launch_grouped<DownSmall>(H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
+        case 3:
+            if (d % 128 == 0) {
+                if (single_m_tile(R, E, 32))
+                    return launch_grouped<DownTinyS>(H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
+                return launch_grouped<DownTiny>(H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
+            }
+            [[fallthrough]];
+        default:
+            if (single_m_tile(R, E, 64))
+                return launch_grouped<DownSmallS>(H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
+            return launch_grouped<DownSmall>(H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
     }
 }
 

@@ -130,9 +130,16 @@ __device__ __forceinline__ int swz(int row) {
 // 64 x 16 bytes land contiguously at LDS byte offset lds_off (wave-uniform, passed in M0).
 // The compiler is not told that this is a memory operation with a counter: the kernels place
 // their own s_waitcnt vmcnt(n) before the barrier that publishes a stage.
+// STREAM marks the line non-temporal: for operand bytes that no other tile will ask for again
+// (weights when every expert has a single m-tile), so that they do not displace reusable lines.
+template <bool STREAM = false>
 __device__ __forceinline__ void dma16(const void* sbase, uint32_t voff, uint32_t lds_off) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                 :: "s"(lds_off), "v"(voff), "s"(sbase) : "memory", "m0");
+    if constexpr (STREAM)
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 nt"
+                     :: "s"(lds_off), "v"(voff), "s"(sbase) : "memory", "m0");
+    else
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                     :: "s"(lds_off), "v"(voff), "s"(sbase) : "memory", "m0");
 }
 
 template <int N> __device__ __forceinline__ void wait_vmcnt() {
@@ -145,10 +152,12 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
 // epilogue of every gate/up tile.
 __device__ __forceinline__ float silu(float a) { return a * __builtin_amdgcn_rcpf(1.0f + __expf(-a)); }
 
-template <int BM_, int BN_, int BK_, int WM_, int WN_, int NSTAGE_, bool DUAL_>
+template <int BM_, int BN_, int BK_, int WM_, int WN_, int NSTAGE_, bool DUAL_,
+          bool STREAM_B_ = false>
 struct Config {
     static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_, NSTAGE = NSTAGE_;
     static constexpr bool DUAL = DUAL_;
+    static constexpr bool STREAM_B = STREAM_B_;            // weights loaded as non-temporal
     static constexpr int NW = WM * WN, NTHREADS = NW * 64;
     static constexpr int WTM = BM / WM, WTN = BN / WN, TM = WTM / 16, TN = WTN / 16;
     static constexpr int KSUB = BK / 32;                   // MFMA k-substeps per stage
@@ -334,7 +343,7 @@ struct LoadPlan {
     // load number n (0 <= n < LA + LB) of k-step kt into the stage at LDS byte offset sbase
     __device__ __forceinline__ void issue_one(int n, uint32_t sbase, size_t koff) const {
         if (n < LA) dma16(a_base + koff, a_voff[n], sbase + a_lds[n]);
-        else dma16(b_base[n - LA] + koff, b_voff[n - LA], sbase + b_lds[n - LA]);
+        else dma16<Cfg::STREAM_B>(b_base[n - LA] + koff, b_voff[n - LA], sbase + b_lds[n - LA]);
     }
     // single loads with explicit LDS region bases (operand rings of different depth)
     __device__ __forceinline__ void issue_a(int i, uint32_t region, size_t koff) const {

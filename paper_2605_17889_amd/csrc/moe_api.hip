@@ -6,7 +6,7 @@
 #include "common.h"
 
 namespace moe {
-void set_gemm_config(int cfg);
+void set_gemm_config(int cfg, int stream_mode);
 }
 
 struct moe_ctx {
@@ -339,11 +339,15 @@ int moe_profile_end(moe_ctx* c, double* stage_ms, int64_t* stage_launches, int32
     return rc;
 }
 
-/* Tuning/testing knob: force the expert-GEMM tile configuration (0 large, 1 medium, 2 small
- * rows-per-expert), or -1 for the automatic choice. All configurations give identical bits. */
+/* Tuning/testing knob: force the expert-GEMM tile configuration (0 large, 1 medium, 2 small,
+ * 3 tiny rows-per-expert), or -1 for the automatic choice; +16 never loads weights as non-temporal,
+ * +32 always does (medium and small tiles). All settings give identical bits. */
 int moe_set_gemm_config(int config) {
-    if (config < -1 || config > 2) return MOE_ERR_INVALID_ARG;
-    moe::set_gemm_config(config);
+    int stream_mode = -1;
+    if (config >= 31) { stream_mode = 1; config -= 32; }
+    else if (config >= 15) { stream_mode = 0; config -= 16; }
+    if (config < -1 || config > 3) return MOE_ERR_INVALID_ARG;
+    moe::set_gemm_config(config, stream_mode);
     return MOE_OK;
 }
 

@@ -208,7 +208,7 @@ def test_permute_bit_exact(T, E, k, seed, empty):
 
 
 # ---------------------------------------------------------------- expert FFN and combine
-@pytest.mark.parametrize("config", [0, 1, 2])
+@pytest.mark.parametrize("config", [0, 1, 2, 3, 2 + 16, 3 + 32])   # +16 / +32: cached / non-temporal weights
 @pytest.mark.parametrize("d,f,rows", [
     (512, 256, [300, 0, 1, 77]),          # empty expert, single row, ragged tails
     (512, 512, [256, 257, 64, 31, 0, 5, 128, 129]),
@@ -251,7 +251,7 @@ def test_expert_ffn_configs_agree_bitwise():
     ctx = B.MoeContext(R, d, f, E, 1)
     outs = []
     try:
-        for config in (0, 1, 2):
+        for config in (0, 1, 2, 3, 1 + 32, 3 + 16):
             B.moe_set_gemm_config(config)
             yp = torch.empty((R, d), dtype=torch.bfloat16, device="cuda")
             B.moe_expert_ffn(ctx, xp, dev(offsets), R, W1, W3, W2, yp)
@@ -259,7 +259,7 @@ def test_expert_ffn_configs_agree_bitwise():
             outs.append(bits(yp))
     finally:
         B.moe_set_gemm_config(-1)
-    assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
+    assert all(np.array_equal(outs[0], o) for o in outs[1:])
     ctx.close()
 
 
