@@ -394,9 +394,11 @@ def test_layer_T0_and_errors():
     ctx.close()
 
 
-def test_layer_mixtral8x7b_decode():
-    cfg = synth.PRESETS["mixtral8x7b_decode"]
-    say("layer 8x7B decode: routing all tokens, FFN on sampled tokens")
+@pytest.mark.parametrize("T", [16, 64, 256])    # 32-row, 32-row and 128-row tile configurations
+def test_layer_mixtral8x7b_decode(T):
+    import dataclasses
+    cfg = dataclasses.replace(synth.PRESETS["mixtral8x7b_decode"], T=T)
+    say(f"layer 8x7B decode T={T}: routing all tokens, FFN on sampled tokens")
     L = synth.make_layer(cfg, "cuda")
     Hh = host_layer(L)
     y, ctx = run_layer(cfg, L)
@@ -405,7 +407,25 @@ def test_layer_mixtral8x7b_decode():
     say(f"    rows per expert {routing['counts'].tolist()}")
     tokens = sample_tokens(cfg, o_ref, p_ref, 6, 1)
     want, _, _ = ref.layer_tokens(Hh["x"], Hh["w_router"], None, Hh["W1"], Hh["W3"], Hh["W2"], cfg.k, tokens)
-    assert_close_ffn(bits(y)[tokens], want, f"8x7B decode ({tokens.size} tokens)")
+    assert_close_ffn(bits(y)[tokens], want, f"8x7B decode T={T} ({tokens.size} tokens)")
+    ctx.close()
+
+
+@pytest.mark.parametrize("preset", ["qwen3_30b_a3b_prefill", "deepseek_v2_lite_prefill"])
+def test_layer_many_small_experts_full_size(preset):
+    """The many-expert presets at the size and launch configuration that bench.py times."""
+    cfg = synth.PRESETS[preset]
+    say(f"layer {preset}: T={cfg.T} E={cfg.E} k={cfg.k}; routing all tokens, FFN on sampled tokens")
+    L = synth.make_layer(cfg, "cuda")
+    Hh = host_layer(L)
+    y, ctx = run_layer(cfg, L)
+    routing = fetch_routing(ctx, cfg.T)
+    _, o_ref, p_ref = check_routing_exact(cfg, Hh, routing, cfg.T)
+    c = routing["counts"]
+    say(f"    rows per expert min {int(c.min())} max {int(c.max())}")
+    tokens = sample_tokens(cfg, o_ref, p_ref, 1, 5)
+    want, _, _ = ref.layer_tokens(Hh["x"], Hh["w_router"], None, Hh["W1"], Hh["W3"], Hh["W2"], cfg.k, tokens)
+    assert_close_ffn(bits(y)[tokens], want, f"{preset} ({tokens.size} tokens)")
     ctx.close()
 
 
