@@ -9,6 +9,7 @@ GEMM, measured with HIP events on the launch stream inside the timed region), pe
 figures, and the CPU oracle timed on the host cores on a bounded token sample.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--micro M]
+                    [--tokens T] [--streamed N] [--planner-sweep] [--gemm-config C]
 """
 import argparse
 import json
@@ -136,6 +137,11 @@ def main():
                     help="run the micro-batched call with this many tokens per micro-batch")
     ap.add_argument("--tokens", type=int, default=0,
                     help="override the preset's token count T (same layer shape and routing recipe)")
+    ap.add_argument("--streamed", type=int, default=0,
+                    help="keep the weights of the last N experts in pinned host memory and move "
+                         "them to the GPU during the call (moe_layer_forward_streamed); adds a "
+                         "'streamed' object with the measured host-to-device rate and the "
+                         "max(compute, transfer) estimate of the paper's Eq. 7")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--gemm-config", type=int, default=-1,
                     help="force the expert-GEMM tile configuration (0 large, 1 medium, 2 small, "
@@ -193,8 +199,44 @@ def main():
         ctx.close()
         return
 
+    streamed = None
+    if args.streamed > 0:
+        if args.micro > 0 or not 0 < args.streamed <= cfg.E:
+            log("bench.py: --streamed needs 1..E experts and no --micro")
+            sys.exit(2)
+        n = args.streamed
+        host_w = [L[m][cfg.E - n:].cpu().contiguous().pin_memory() for m in ("W1", "W3", "W2")]
+        dev_w = [L[m][:cfg.E - n] if n < cfg.E else None for m in ("W1", "W3", "W2")]
+        # host-to-device rate of this machine, alone: one expert's three matrices, pinned
+        probe = torch.empty(host_w[0][0].numel(), dtype=torch.bfloat16, device="cuda")
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        reps = 0
+        while reps < 3 * n:
+            for hw in host_w:
+                probe.copy_(hw[reps // 3 % n].view(-1), non_blocking=True)
+                reps += 1
+        torch.cuda.synchronize()
+        h2d = reps * probe.numel() * 2 / (time.perf_counter() - t0)
+        # all experts resident, same shape: the computation side of the estimate
+        for _ in range(3):
+            B.moe_layer_forward(ctx, L["x"], L["w_router"], L["bias"], L["W1"], L["W3"], L["W2"], T, y)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(10):
+            B.moe_layer_forward(ctx, L["x"], L["w_router"], L["bias"], L["W1"], L["W3"], L["W2"], T, y)
+        torch.cuda.synchronize()
+        resident_ms = (time.perf_counter() - t0) / 10 * 1e3
+        moved = n * 3 * cfg.d_model * cfg.d_ff * 2
+        streamed = {"n_streamed": n, "bytes_moved_per_step": moved, "h2d_GB/s_measured": h2d / 1e9,
+                    "t_load_ms": moved / h2d * 1e3, "t_resident_ms": resident_ms,
+                    "estimate_ms": max(moved / h2d * 1e3, resident_ms)}
+
     def step():
-        if args.micro > 0:
+        if streamed is not None:
+            B.moe_layer_forward_streamed(ctx, L["x"], L["w_router"], L["bias"], *dev_w, *host_w,
+                                         args.streamed, T, y)
+        elif args.micro > 0:
             B.moe_layer_forward_microbatched(ctx, L["x"], L["w_router"], L["bias"], L["W1"], L["W3"],
                                              L["W2"], T, args.micro, y)
         else:
@@ -254,6 +296,9 @@ def main():
         "roofline": roofline,
         "stages": stages,
     }
+    if streamed is not None:
+        streamed["measured_over_estimate"] = ms_per_step / streamed["estimate_ms"]
+        out["streamed"] = streamed
     if not args.no_cpu_baseline:
         log("[bench] timing the CPU oracle on a token sample")
         out["cpu_baseline"] = cpu_baseline(cfg, L)

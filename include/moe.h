@@ -143,6 +143,27 @@ int moe_layer_forward_microbatched(moe_ctx* ctx, const moe_bf16* x, const float*
                                    const moe_bf16* W2, int32_t T, int32_t micro_tokens,
                                    moe_bf16* y, void* stream);
 
+/* moe_layer_forward with the weights of the last `n_streamed` experts kept in pinned host memory
+ * and moved to the GPU while the other experts compute (the expert group that the paper's
+ * Section 4.1.1 moves over PCIe: Eq. 7 prices the transfer at D_Y per moved expert over the PCIe
+ * bandwidth, and transfer and computation overlap). Experts [0, E - n_streamed) are resident:
+ * W1, W3 [E - n_streamed, d_ff, d_model], W2 [E - n_streamed, d_model, d_ff] in device memory
+ * (ignored, may be NULL, when n_streamed == E). Experts [E - n_streamed, E) are read from
+ * W1_host, W3_host [n_streamed, d_ff, d_model], W2_host [n_streamed, d_model, d_ff]: HOST pointers
+ * to page-locked memory (hipHostMalloc or an equivalent allocator; pageable memory makes the
+ * copies synchronous), which must stay unchanged until the work enqueued by the call has finished.
+ * The first call allocates two device staging slots of 3*d_model*d_ff*2 bytes each, a copy
+ * stream and four events, kept until moe_destroy (MOE_ERR_WORKSPACE if the allocation fails).
+ * Transfers run on the library's copy stream; all kernels run on `stream`, resident experts
+ * first, then each streamed expert as its weights arrive. The output equals moe_layer_forward's
+ * bit for bit (same kernels, same accumulation chains). 0 <= n_streamed <= E. Calls on one
+ * context must be enqueued from one host thread at a time. */
+int moe_layer_forward_streamed(moe_ctx* ctx, const moe_bf16* x, const float* w_router,
+                               const float* bias, const moe_bf16* W1, const moe_bf16* W3,
+                               const moe_bf16* W2, const moe_bf16* W1_host,
+                               const moe_bf16* W3_host, const moe_bf16* W2_host,
+                               int32_t n_streamed, int32_t T, moe_bf16* y, void* stream);
+
 /* Copy the routing tables that the last moe_layer_forward call on this context left in the
  * workspace into caller tensors (device-to-device copies enqueued on `stream`); for the
  * micro-batched call they are the tables of its last micro-batch. T is that call's token count.

@@ -22,7 +22,7 @@ EXPORTS = (
     "moe_create", "moe_destroy", "moe_workspace_bytes", "moe_status_string", "moe_route",
     "moe_route_from_logits", "moe_permute", "moe_expert_ffn", "moe_combine", "moe_layer_forward",
     "moe_layer_forward_microbatched", "moe_last_routing", "moe_profile_begin", "moe_profile_end",
-    "moe_set_gemm_config", "moe_estimate_expert_stage",
+    "moe_set_gemm_config", "moe_estimate_expert_stage", "moe_layer_forward_streamed",
 )
 
 
@@ -187,6 +187,25 @@ def moe_layer_forward_microbatched(ctx: MoeContext, x, w_router, bias, W1, W3, W
         _ptr(bias, torch.float32, "bias"), _ptr(W1, torch.bfloat16, "W1"), _ptr(W3, torch.bfloat16, "W3"),
         _ptr(W2, torch.bfloat16, "W2"), C.c_int32(T), C.c_int32(micro_tokens),
         _ptr(y, torch.bfloat16, "y"), _stream(stream)), "moe_layer_forward_microbatched")
+
+
+def _host_ptr(t: torch.Tensor, dtype: torch.dtype, what: str):
+    if t.is_cuda or t.dtype != dtype or not t.is_contiguous() or not t.is_pinned():
+        raise MoeError(f"{what}: expected a contiguous pinned host tensor of {dtype}")
+    return C.c_void_p(t.data_ptr())
+
+
+def moe_layer_forward_streamed(ctx: MoeContext, x, w_router, bias, W1, W3, W2, W1_host, W3_host,
+                               W2_host, n_streamed, T, y, stream=None):
+    """Last n_streamed experts' weights in pinned host tensors; the others (device) may be None
+    when every expert is streamed."""
+    hp = (lambda t, n: C.c_void_p(0)) if n_streamed == 0 else (lambda t, n: _host_ptr(t, torch.bfloat16, n))
+    _check(lib().moe_layer_forward_streamed(
+        ctx._h, _ptr(x, torch.bfloat16, "x"), _ptr(w_router, torch.float32, "w_router"),
+        _ptr(bias, torch.float32, "bias"), _ptr(W1, torch.bfloat16, "W1"), _ptr(W3, torch.bfloat16, "W3"),
+        _ptr(W2, torch.bfloat16, "W2"), hp(W1_host, "W1_host"), hp(W3_host, "W3_host"),
+        hp(W2_host, "W2_host"), C.c_int32(n_streamed), C.c_int32(T), _ptr(y, torch.bfloat16, "y"),
+        _stream(stream)), "moe_layer_forward_streamed")
 
 
 def moe_last_routing(ctx: MoeContext, T, topk_idx=None, topk_w=None, counts=None, offsets=None,

@@ -113,35 +113,37 @@ void set_gemm_config(int cfg, int stream_mode) {
 
 // `a` is the grouped activation matrix [R, d] when row_index is NULL; otherwise it is the
 // token matrix [T, d] and grouped row p reads token row_index[p] / index_div (the caller makes
-// sure that T * d * 2 bytes fit a 32-bit offset).
+// sure that T * d * 2 bytes fit a 32-bit offset). R bounds the rows of the E launched experts
+// (it sizes the grid); R_hint is how many rows they are expected to hold together (it picks the
+// tile configuration): the two differ when a call covers a subset of a layer's experts.
 int launch_gateup(const moe_bf16* a, const int32_t* row_index, int index_div,
-                  const int32_t* offsets, int R, int d, int f, int E, const moe_bf16* W1,
-                  const moe_bf16* W3, moe_bf16* H, hipStream_t s) {
+                  const int32_t* offsets, int R, int R_hint, int d, int f, int E,
+                  const moe_bf16* W1, const moe_bf16* W3, moe_bf16* H, hipStream_t s) {
     if (R == 0) return MOE_OK;
     const moe_bf16* x_perm = a;
-    int config = pick_config(R, E);
+    int config = pick_config(R_hint, E);
     if (config == 0 && d / 64 < 3) config = 1;     // the pipelined kernel needs three k-steps
     switch (config) {
         case 0: return launch_grouped<GateUpLarge, 2, 3>(x_perm, W1, W3, H, offsets, row_index, index_div, R, E, f, d, s);
         case 1:
-            if (single_m_tile(R, E, 128))
+            if (single_m_tile(R_hint, E, 128))
                 return launch_grouped<GateUpMidS>(x_perm, W1, W3, H, offsets, row_index, index_div, R, E, f, d, s);
             return launch_grouped<GateUpMid>(x_perm, W1, W3, H, offsets, row_index, index_div, R, E, f, d, s);
         case 3:
-            if (single_m_tile(R, E, 32))
+            if (single_m_tile(R_hint, E, 32))
                 return launch_grouped<GateUpTinyS>(x_perm, W1, W3, H, offsets, row_index, index_div, R, E, f, d, s);
             return launch_grouped<GateUpTiny>(x_perm, W1, W3, H, offsets, row_index, index_div, R, E, f, d, s);
         default:
-            if (single_m_tile(R, E, 64))
+            if (single_m_tile(R_hint, E, 64))
                 return launch_grouped<GateUpSmallS>(x_perm, W1, W3, H, offsets, row_index, index_div, R, E, f, d, s);
             return launch_grouped<GateUpSmall>(x_perm, W1, W3, H, offsets, row_index, index_div, R, E, f, d, s);
     }
 }
 
-int launch_down(const moe_bf16* H, const int32_t* offsets, int R, int d, int f, int E,
+int launch_down(const moe_bf16* H, const int32_t* offsets, int R, int R_hint, int d, int f, int E,
                 const moe_bf16* W2, moe_bf16* y_perm, hipStream_t s) {
     if (R == 0) return MOE_OK;
-    int config = pick_config(R, E);
+    int config = pick_config(R_hint, E);
     if (config == 0 && f / 64 < 3) config = 1;     // the pipelined kernel needs three k-steps
     switch (config) {
         case 0: return launch_grouped<DownLarge, 2, 3>(H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
@@ -149,22 +151,22 @@ int launch_down(const moe_bf16* H, const int32_t* offsets, int R, int d, int f, 
             // HBM-bound: wide tiles stream more bytes per workgroup, but only if there are
             // enough of them to occupy the 256 compute units (about one m-tile per expert).
             if (static_cast<long long>(E) * (d / 256) >= 160 && d % 256 == 0) {
-                if (single_m_tile(R, E, 128))
+                if (single_m_tile(R_hint, E, 128))
                     return launch_grouped<DownMidWideS>(H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
                 return launch_grouped<DownMidWide>(H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
             }
-            if (single_m_tile(R, E, 128))
+            if (single_m_tile(R_hint, E, 128))
                 return launch_grouped<DownMidS>(H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
             return launch_grouped<DownMid>(H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
         case 3:
             if (d % 128 == 0) {
-                if (single_m_tile(R, E, 32))
+                if (single_m_tile(R_hint, E, 32))
                     return launch_grouped<DownTinyS>(H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
                 return launch_grouped<DownTiny>(H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
             }
             [[fallthrough]];
         default:
-            if (single_m_tile(R, E, 64))
+            if (single_m_tile(R_hint, E, 64))
                 return launch_grouped<DownSmallS>(H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
             return launch_grouped<DownSmall>(H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
     }

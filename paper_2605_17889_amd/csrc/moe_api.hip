@@ -32,6 +32,12 @@ struct moe_ctx {
     std::vector<hipEvent_t> prof_events;       // per recorded interval: start, stop
     std::vector<int> prof_stage;               // stage of each interval
     int64_t prof_launches[MOE_NUM_STAGES];
+    // streamed experts (created by the first moe_layer_forward_streamed call, kept until destroy)
+    hipStream_t copy_stream;
+    unsigned char* slot[2];     // device staging, each W1_e | W3_e | W2_e of one expert
+    hipEvent_t ready[2];        // recorded on copy_stream: the slot holds its expert
+    hipEvent_t freed[2];        // recorded on the caller's stream: the slot's GEMMs are enqueued
+    bool freed_valid[2];
 };
 
 namespace {
@@ -120,17 +126,36 @@ int forward_chunk(moe_ctx* c, const moe_bf16* x, const float* w_router, const fl
     }
     rc = run_stage(c, MOE_STAGE_GATEUP, 1, s, [&] {
         return fuse_gather
-                   ? launch_gateup(x, c->perm, k, c->offsets, R, d, f, E, W1, W3, c->H, s)
-                   : launch_gateup(c->x_perm, nullptr, 1, c->offsets, R, d, f, E, W1, W3, c->H, s);
+                   ? launch_gateup(x, c->perm, k, c->offsets, R, R, d, f, E, W1, W3, c->H, s)
+                   : launch_gateup(c->x_perm, nullptr, 1, c->offsets, R, R, d, f, E, W1, W3, c->H, s);
     });
     if (rc != MOE_OK) return rc;
     rc = run_stage(c, MOE_STAGE_DOWN, 1, s, [&] {
-        return launch_down(c->H, c->offsets, R, d, f, E, W2, c->y_perm, s);
+        return launch_down(c->H, c->offsets, R, R, d, f, E, W2, c->y_perm, s);
     });
     if (rc != MOE_OK) return rc;
     return run_stage(c, MOE_STAGE_COMBINE, 1, s, [&] {
         return launch_combine(c->y_perm, c->inv_perm, c->topk_w, T, d, k, y, s);
     });
+}
+
+int ensure_streaming(moe_ctx* c) {
+    if (c->copy_stream) return MOE_OK;
+    const size_t bytes = static_cast<size_t>(3) * c->shape.d_model * c->shape.d_ff * sizeof(moe_bf16);
+    void* p = nullptr;
+    if (hipMalloc(&p, 2 * bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        return MOE_ERR_WORKSPACE;
+    }
+    c->slot[0] = static_cast<unsigned char*>(p);
+    c->slot[1] = c->slot[0] + bytes;
+    for (int i = 0; i < 2; ++i) {
+        MOE_HIP_TRY(hipEventCreateWithFlags(&c->ready[i], hipEventDisableTiming));
+        MOE_HIP_TRY(hipEventCreateWithFlags(&c->freed[i], hipEventDisableTiming));
+        c->freed_valid[i] = false;
+    }
+    MOE_HIP_TRY(hipStreamCreateWithFlags(&c->copy_stream, hipStreamNonBlocking));   // default priority
+    return MOE_OK;
 }
 
 }  // namespace
@@ -189,6 +214,8 @@ int moe_create(moe_ctx** out, const moe_shape* shape, int device_id) {
     c->prof_armed = false;
     c->prof_max_calls = c->prof_calls = 0;
     for (auto& v : c->prof_launches) v = 0;
+    c->copy_stream = nullptr;
+    c->slot[0] = c->slot[1] = nullptr;
     *out = c;
     return MOE_OK;
 }
@@ -197,6 +224,15 @@ int moe_destroy(moe_ctx* c) {
     if (!c) return MOE_ERR_INVALID_ARG;
     for (hipEvent_t e : c->prof_events) (void)hipEventDestroy(e);
     int rc = MOE_OK;
+    if (c->copy_stream) {
+        if (hipStreamSynchronize(c->copy_stream) != hipSuccess) rc = MOE_ERR_HIP;
+        (void)hipStreamDestroy(c->copy_stream);
+        for (int i = 0; i < 2; ++i) {
+            (void)hipEventDestroy(c->ready[i]);
+            (void)hipEventDestroy(c->freed[i]);
+        }
+    }
+    if (c->slot[0] && hipFree(c->slot[0]) != hipSuccess) rc = MOE_ERR_HIP;
     if (c->base && hipFree(c->base) != hipSuccess) rc = MOE_ERR_HIP;
     delete c;
     return rc;
@@ -245,9 +281,9 @@ int moe_expert_ffn(moe_ctx* c, const moe_bf16* x_perm, const int32_t* offsets, i
     if (!x_perm || !offsets || !W1 || !W3 || !W2 || !y_perm) return MOE_ERR_INVALID_ARG;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const moe_shape& sh = c->shape;
-    int rc = launch_gateup(x_perm, nullptr, 1, offsets, R, sh.d_model, sh.d_ff, sh.E, W1, W3, c->H, s);
+    int rc = launch_gateup(x_perm, nullptr, 1, offsets, R, R, sh.d_model, sh.d_ff, sh.E, W1, W3, c->H, s);
     if (rc != MOE_OK) return rc;
-    return launch_down(c->H, offsets, R, sh.d_model, sh.d_ff, sh.E, W2, y_perm, s);
+    return launch_down(c->H, offsets, R, R, sh.d_model, sh.d_ff, sh.E, W2, y_perm, s);
 }
 
 int moe_combine(moe_ctx* c, const moe_bf16* y_perm, const int32_t* inv_perm, const float* topk_w,
@@ -285,6 +321,79 @@ int moe_layer_forward_microbatched(moe_ctx* c, const moe_bf16* x, const float* w
         if (rc != MOE_OK) return rc;
     }
     return MOE_OK;
+}
+
+int moe_layer_forward_streamed(moe_ctx* c, const moe_bf16* x, const float* w_router,
+                               const float* bias, const moe_bf16* W1, const moe_bf16* W3,
+                               const moe_bf16* W2, const moe_bf16* W1_host,
+                               const moe_bf16* W3_host, const moe_bf16* W2_host,
+                               int32_t n_streamed, int32_t T, moe_bf16* y, void* stream) {
+    if (!c || T < 0 || T > c->shape.T_max || n_streamed < 0 || n_streamed > c->shape.E)
+        return MOE_ERR_INVALID_ARG;
+    if (T == 0) return MOE_OK;
+    const moe_shape& sh = c->shape;
+    const int d = sh.d_model, f = sh.d_ff, E = sh.E, k = sh.k, R = T * k;
+    const int E_res = E - n_streamed;
+    if (!x || !w_router || !y) return MOE_ERR_INVALID_ARG;
+    if (E_res > 0 && (!W1 || !W3 || !W2)) return MOE_ERR_INVALID_ARG;
+    if (n_streamed > 0 && (!W1_host || !W3_host || !W2_host)) return MOE_ERR_INVALID_ARG;
+    // the fused row gather addresses token rows with 32-bit byte offsets
+    if (static_cast<unsigned long long>(T) * d * 2ull >= (1ull << 32)) return MOE_ERR_UNSUPPORTED_SHAPE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (n_streamed > 0) {
+        const int rc = ensure_streaming(c);
+        if (rc != MOE_OK) return rc;
+    }
+    if (c->prof_armed) c->prof_calls++;
+    const size_t per = static_cast<size_t>(d) * f;              // elements of one expert matrix
+    auto enqueue_copy = [&](int j) -> int {                    // streamed expert j -> slot j % 2
+        const int b = j & 1;
+        if (c->freed_valid[b]) MOE_HIP_TRY(hipStreamWaitEvent(c->copy_stream, c->freed[b], 0));
+        moe_bf16* dst = reinterpret_cast<moe_bf16*>(c->slot[b]);
+        const size_t bytes = per * sizeof(moe_bf16);
+        MOE_HIP_TRY(hipMemcpyAsync(dst, W1_host + j * per, bytes, hipMemcpyHostToDevice, c->copy_stream));
+        MOE_HIP_TRY(hipMemcpyAsync(dst + per, W3_host + j * per, bytes, hipMemcpyHostToDevice, c->copy_stream));
+        MOE_HIP_TRY(hipMemcpyAsync(dst + 2 * per, W2_host + j * per, bytes, hipMemcpyHostToDevice, c->copy_stream));
+        MOE_HIP_TRY(hipEventRecord(c->ready[b], c->copy_stream));
+        return MOE_OK;
+    };
+    int rc;
+    // The first two transfers start at once and run under the routing and the resident experts.
+    for (int j = 0; j < n_streamed && j < 2; ++j)
+        if ((rc = enqueue_copy(j)) != MOE_OK) return rc;
+    rc = run_stage(c, MOE_STAGE_ROUTE, 1, s, [&] {
+        return launch_route(x, w_router, bias, T, d, E, k, c->topk_idx, c->topk_w, nullptr, c->logits, s);
+    });
+    if (rc != MOE_OK) return rc;
+    rc = run_stage(c, MOE_STAGE_PERMUTE, 3, s, [&] {
+        return launch_permute(c->topk_idx, R, E, c->counts, c->offsets, c->perm, c->inv_perm,
+                              c->scratch, s);
+    });
+    if (rc != MOE_OK) return rc;
+    // experts [e0, e0 + n) with weights at w1/w3/w2; rows outside those groups are not touched
+    auto ffn = [&](int e0, int n, const moe_bf16* w1, const moe_bf16* w3, const moe_bf16* w2) -> int {
+        const int hint = static_cast<int>(static_cast<long long>(R) * n / E);
+        int r = run_stage(c, MOE_STAGE_GATEUP, 1, s, [&] {
+            return launch_gateup(x, c->perm, k, c->offsets + e0, R, hint, d, f, n, w1, w3, c->H, s);
+        });
+        if (r != MOE_OK) return r;
+        return run_stage(c, MOE_STAGE_DOWN, 1, s, [&] {
+            return launch_down(c->H, c->offsets + e0, R, hint, d, f, n, w2, c->y_perm, s);
+        });
+    };
+    if (E_res > 0 && (rc = ffn(0, E_res, W1, W3, W2)) != MOE_OK) return rc;
+    for (int j = 0; j < n_streamed; ++j) {
+        const int b = j & 1;
+        MOE_HIP_TRY(hipStreamWaitEvent(s, c->ready[b], 0));
+        const moe_bf16* w = reinterpret_cast<const moe_bf16*>(c->slot[b]);
+        if ((rc = ffn(E_res + j, 1, w, w + per, w + 2 * per)) != MOE_OK) return rc;
+        MOE_HIP_TRY(hipEventRecord(c->freed[b], s));
+        c->freed_valid[b] = true;
+        if (j + 2 < n_streamed && (rc = enqueue_copy(j + 2)) != MOE_OK) return rc;
+    }
+    return run_stage(c, MOE_STAGE_COMBINE, 1, s, [&] {
+        return launch_combine(c->y_perm, c->inv_perm, c->topk_w, T, d, k, y, s);
+    });
 }
 
 int moe_last_routing(moe_ctx* c, int32_t T, int32_t* topk_idx, float* topk_w, int32_t* counts,

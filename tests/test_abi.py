@@ -79,6 +79,8 @@ def test_null_arguments_are_rejected_before_any_gpu_work(lib):
     assert lib.moe_create(None, None, 0) == -1
     assert lib.moe_destroy(None) == -1
     assert lib.moe_layer_forward(None, None, None, None, None, None, None, 4, None, None) == -1
+    assert lib.moe_layer_forward_streamed(None, None, None, None, None, None, None, None, None, None,
+                                          1, 4, None, None) == -1
     assert lib.moe_set_gemm_config(9) == -1
     assert lib.moe_set_gemm_config(4 + 32) == -1
     for ok in (0, 3, 1 + 16, -1 + 32, -1):

@@ -478,6 +478,47 @@ def test_layer_mixtral8x22b_coalesced_vs_microbatched(experts_8x22b):
     ctx.close()
 
 
+def pinned_tail(W, n):
+    return W[W.shape[0] - n:].cpu().contiguous().pin_memory()
+
+
+@pytest.mark.parametrize("n_streamed", [0, 1, 3, 8])
+def test_layer_streamed_experts_tiny_bitwise(n_streamed):
+    """Experts whose weights arrive from pinned host memory give the bits of the resident call;
+    repeated calls reuse the two staging slots."""
+    cfg = synth.PRESETS["tiny"]
+    say(f"layer tiny, last {n_streamed} experts streamed from host memory")
+    L = synth.make_layer(cfg, "cuda")
+    y_res, ctx = run_layer(cfg, L)
+    E = cfg.E
+    host = [pinned_tail(L[n], n_streamed) if n_streamed else None for n in ("W1", "W3", "W2")]
+    dev_w = [L[n][:E - n_streamed].contiguous() if n_streamed < E else None for n in ("W1", "W3", "W2")]
+    for T in (cfg.T, 100, cfg.T):
+        want = y_res if T == cfg.T else run_layer(cfg, L, T=T, ctx=ctx)[0]
+        y = torch.full((T, cfg.d_model), float("nan"), dtype=torch.bfloat16, device="cuda")
+        B.moe_layer_forward_streamed(ctx, L["x"][:T].contiguous(), L["w_router"], L["bias"], *dev_w, *host,
+                                     n_streamed, T, y)
+        torch.cuda.synchronize()
+        assert np.array_equal(bits(y), bits(want)), f"T={T}"
+    ctx.close()
+
+
+def test_layer_streamed_experts_8x22b_bitwise(experts_8x22b):
+    cfg = synth.PRESETS["mixtral8x22b_prefill"]
+    say("layer 8x22B prefill, last 2 experts streamed from host memory")
+    L, _ = layer_8x22b(cfg, experts_8x22b)
+    y_res, ctx = run_layer(cfg, L)
+    n = 2
+    host = [pinned_tail(L[m], n) for m in ("W1", "W3", "W2")]
+    dev_w = [L[m][:cfg.E - n] for m in ("W1", "W3", "W2")]
+    for _ in range(2):
+        y = torch.full((cfg.T, cfg.d_model), float("nan"), dtype=torch.bfloat16, device="cuda")
+        B.moe_layer_forward_streamed(ctx, L["x"], L["w_router"], None, *dev_w, *host, n, cfg.T, y)
+        torch.cuda.synchronize()
+        assert np.array_equal(bits(y), bits(y_res))
+    ctx.close()
+
+
 @pytest.mark.parametrize("preset", ["mixtral8x22b_zipf", "mixtral8x22b_zipf_empty"])
 def test_layer_mixtral8x22b_zipf(experts_8x22b, preset):
     cfg = synth.PRESETS[preset]
