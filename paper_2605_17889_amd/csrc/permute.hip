@@ -7,6 +7,7 @@
 // running counts of experts l, l+64, l+128, l+192 (E <= 256).
 //   1. hist   : seg_hist[g][e] = ids of segment g routed to e          (ballot + popcount)
 //   2. scan   : counts, offsets, and seg_base[g][e] = offsets[e] + sum_{g'<g} seg_hist[g'][e]
+//               (one block; experts across lanes, slices of the segment range side by side)
 //   3. scatter: position = seg_base[g][e] + rank of the id among equal experts in the segment
 // Ids whose expert index is outside [0,E) are dropped (inv_perm = -1).
 #include "common.h"
@@ -81,55 +82,77 @@ __global__ __launch_bounds__(kBlockWaves* kWave) void hist_kernel(
         if (w * kWave + lane < E) seg_hist[static_cast<size_t>(seg) * E + w * kWave + lane] = cnt[w];
 }
 
-// One block of 1024 threads (16 wavefronts). Wavefront w scans the columns e = w, w+16, ...
+// One block of 1024 threads. Thread (q, e) = (tid / E, tid % E) walks the segments of slice q
+// of the segment range for expert e, so consecutive lanes read consecutive experts of a row of
+// seg_hist (coalesced) and the 1024 / E slices run side by side; the slices' sums are then
+// prefix-summed per expert, the experts' totals across experts, and a second walk writes
+// seg_base. All integer: any summation order gives the same bits.
 __global__ __launch_bounds__(1024) void scan_kernel(const int32_t* __restrict__ seg_hist,
                                                     int nseg, int E, int32_t* __restrict__ counts,
                                                     int32_t* __restrict__ offsets,
                                                     int32_t* __restrict__ seg_base) {
+    __shared__ int32_t part[1024];              // [slice][expert]: sum, then exclusive prefix
     __shared__ int32_t tot[kMaxExperts];
     __shared__ int32_t off[kMaxExperts + 1];
-    const int lane = threadIdx.x & (kWave - 1);
-    const int w = threadIdx.x / kWave;
-    for (int e = w; e < E; e += 16) {
+    const int tid = threadIdx.x;
+    const int slices = min(1024 / E, 32);       // >= 4 because E <= 256; 32 bound the serial
+                                                // pass over the slices below
+    const int e = tid % E, q = tid / E;
+    const bool active = q < slices;
+    const int per = (nseg + slices - 1) / slices;
+    const int g0 = min(nseg, q * per), g1 = min(nseg, g0 + per);
+    if (active) {
         int sum = 0;
-#pragma unroll 4
-        for (int g = lane; g < nseg; g += kWave) sum += seg_hist[static_cast<size_t>(g) * E + e];
-        for (int s = 32; s >= 1; s >>= 1) sum += __shfl_xor(sum, s, kWave);
-        if (lane == 0) tot[e] = sum;
+#pragma unroll 8
+        for (int g = g0; g < g1; ++g) sum += seg_hist[static_cast<size_t>(g) * E + e];
+        part[q * E + e] = sum;
     }
     __syncthreads();
-    if (threadIdx.x == 0) {
+    if (tid < E) {                              // slices of one expert, in order
         int run = 0;
-        for (int e = 0; e < E; ++e) {
-            off[e] = run;
-            counts[e] = tot[e];
-            offsets[e] = run;
-            run += tot[e];
+        for (int i = 0; i < slices; ++i) {
+            const int v = part[i * E + tid];
+            part[i * E + tid] = run;
+            run += v;
         }
-        off[E] = run;
-        offsets[E] = run;
+        tot[tid] = run;
     }
     __syncthreads();
-    for (int e = w; e < E; e += 16) {
-        int carry = off[e];
-        for (int g0 = 0; g0 < nseg; g0 += 4 * kWave) {     // four independent loads in flight
-            int v4[4];
+    if (tid < kWave) {                          // exclusive prefix over the experts, 4 per lane
+        int mine[kExpertWords], sum = 0;
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int g = g0 + u * kWave + lane;
-                v4[u] = (g < nseg) ? seg_hist[static_cast<size_t>(g) * E + e] : 0;
-            }
+        for (int w = 0; w < kExpertWords; ++w) {
+            const int x = tid * kExpertWords + w;
+            mine[w] = x < E ? tot[x] : 0;
+            sum += mine[w];
+        }
+        int incl = sum;
+        for (int s = 1; s < kWave; s <<= 1) {
+            const int up = __shfl_up(incl, s, kWave);
+            if (tid >= s) incl += up;
+        }
+        int run = incl - sum;
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int g = g0 + u * kWave + lane;
-                int incl = v4[u];                          // inclusive prefix over the 64 lanes
-                for (int s = 1; s < kWave; s <<= 1) {
-                    const int up = __shfl_up(incl, s, kWave);
-                    if (lane >= s) incl += up;
-                }
-                if (g < nseg) seg_base[static_cast<size_t>(g) * E + e] = carry + incl - v4[u];
-                carry += __shfl(incl, kWave - 1, kWave);
-            }
+        for (int w = 0; w < kExpertWords; ++w) {
+            const int x = tid * kExpertWords + w;
+            if (x < E) off[x] = run;
+            run += mine[w];
+        }
+        if (tid == kWave - 1) off[E] = incl;
+    }
+    __syncthreads();
+    if (tid < E) {
+        counts[tid] = tot[tid];
+        offsets[tid] = off[tid];
+    }
+    if (tid == 0) offsets[E] = off[E];
+    if (active) {
+        int run = off[e] + part[q * E + e];
+#pragma unroll 8
+        for (int g = g0; g < g1; ++g) {
+            const int v = seg_hist[static_cast<size_t>(g) * E + e];
+            seg_base[static_cast<size_t>(g) * E + e] = run;
+            run += v;
         }
     }
 }
