@@ -28,7 +28,7 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E peak
 # scaled by what the same counter reads for a plain 1 GiB copy: 2.00 and 1.00). Measured with the
 # commands recorded in profiles/expert_gemm_mixtral8x22b_prefill_hbm_traffic.md; it cannot be
 # measured from inside this process, so workloads without a recorded value report null.
-MEASURED_TRAFFIC_BYTES = {"mixtral8x22b_prefill": 13.42e9 + 0.557e9}
+MEASURED_TRAFFIC_BYTES = {"mixtral8x22b_prefill": 11.79e9 + 0.592e9}
 
 
 def log(*a):
@@ -80,7 +80,7 @@ def cpu_baseline(cfg, L, target_seconds=15.0):
 
 
 SUSTAINED_TFLOPS = 1330.0      # this library's gate/up kernel on large uniform expert groups
-SUSTAINED_GBS = 5400.0         # this library's weight streaming at 64 rows per expert
+SUSTAINED_GBS = 6100.0         # this library's weight streaming at 64 rows per expert
 
 
 def planner_sweep(args, cfg, L, ctx, y, B, torch):
