@@ -11,8 +11,10 @@
  *
  * Conventions for every entry point
  *   - All tensor pointers are DEVICE pointers on the context's GPU, owned by the caller,
- *     row-major, densely packed. bf16 tensors are raw 16-bit patterns (moe_bf16).
- *     The library never frees or keeps a caller pointer after the call returns.
+ *     row-major, densely packed (the one exception: the *_host arguments of
+ *     moe_layer_forward_streamed are HOST pointers to page-locked memory). bf16 tensors are
+ *     raw 16-bit patterns (moe_bf16). The library never frees a caller pointer and never uses
+ *     one after the work that the call enqueued has finished.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream). Calls enqueue
  *     work and return without synchronising the host; results are ready when the stream is.
  *   - Return value: MOE_OK or a negative moe_status. Arguments are checked on the host
@@ -38,7 +40,8 @@
 extern "C" {
 #endif
 
-typedef struct moe_ctx moe_ctx;     /* opaque; owns only its own device workspace */
+typedef struct moe_ctx moe_ctx;     /* opaque; owns only its own device workspace, events and
+                                       (after a streamed call) a copy stream */
 typedef uint16_t moe_bf16;          /* raw bfloat16 bits */
 
 typedef struct {
