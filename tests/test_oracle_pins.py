@@ -121,6 +121,28 @@ def test_topk_equals_full_sort_and_gate_identities():
             assert np.allclose(g[:, 0], 1 / (1 + np.exp(l1 - l0)), atol=1e-7)
 
 
+@pytest.mark.parametrize("E,ks", [(128, (1, 8, 64)), (200, (6, 33)), (256, (64,))])
+def test_topk_many_experts_equals_full_sort(E, ks):
+    """The same brute force with more than 64 experts (several experts per lane on the GPU),
+    planted ties across the 64-expert boundaries and a row of all-equal logits."""
+    rng = np.random.default_rng(E)
+    T = 120
+    lg = rng.normal(0, 1.5, size=(T, E)).astype(np.float32)
+    lg[::5, 3] = lg[::5, 67]
+    lg[::5, E - 1] = lg[::5, 3]
+    lg[1::9] = np.round(lg[1::9])
+    lg[7] = 0.25
+    for k in ks:
+        idx, g = ref.topk(lg, k)
+        order = np.argsort(-lg.astype(np.float64), axis=1, kind="stable")[:, :k]
+        assert np.array_equal(idx, order)
+        assert np.all(np.abs(g.sum(1) - 1) <= 1e-5)
+        assert np.allclose(g[7], 1.0 / k, atol=1e-7) and idx[7].tolist() == list(range(k))
+        sel = np.take_along_axis(lg.astype(np.float64), idx.astype(np.int64), 1)
+        w = np.exp(sel - sel[:, :1])
+        assert np.allclose(g, w / w.sum(1, keepdims=True), atol=1e-7)
+
+
 # ----------------------------------------------------------------------------- permutation
 def test_permute_worked_example():
     c = _load("permute_worked_example.json")
@@ -129,7 +151,8 @@ def test_permute_worked_example():
     assert perm.tolist() == c["perm"] and inv.tolist() == c["inv_perm"]
 
 
-@pytest.mark.parametrize("T,E,k,seed", [(1, 4, 1, 0), (37, 8, 2, 1), (1000, 64, 6, 2), (513, 3, 3, 3)])
+@pytest.mark.parametrize("T,E,k,seed", [(1, 4, 1, 0), (37, 8, 2, 1), (1000, 64, 6, 2), (513, 3, 3, 3),
+                                        (700, 128, 8, 4), (300, 256, 64, 5), (90, 200, 5, 6)])
 def test_permute_matches_stable_sort_and_invariants(T, E, k, seed):
     rng = np.random.default_rng(seed)
     idx = np.stack([rng.permutation(E)[:k] for _ in range(T)]).astype(np.int32)
@@ -233,7 +256,7 @@ def _dense_bruteforce(x, lg, W1, W3, W2, k):
     return y
 
 
-@pytest.mark.parametrize("E,k", [(8, 2), (5, 3), (4, 4)])
+@pytest.mark.parametrize("E,k", [(8, 2), (5, 3), (4, 4), (128, 8), (64, 6)])
 def test_layer_equals_dense_bruteforce(E, k):
     rng = np.random.default_rng(100 + E)
     T, d, f = 24, 512, 40
