@@ -142,6 +142,9 @@ def main():
                          "them to the GPU during the call (moe_layer_forward_streamed); adds a "
                          "'streamed' object with the measured host-to-device rate and the "
                          "max(compute, transfer) estimate of the paper's Eq. 7")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step into a HIP graph after the warm-up and time replays "
+                         "(per-stage event timing is off in this mode)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--gemm-config", type=int, default=-1,
                     help="force the expert-GEMM tile configuration (0 large, 1 medium, 2 small, "
@@ -245,13 +248,36 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    B.moe_profile_begin(ctx, args.steps)
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    stage_ms, launches, calls = B.moe_profile_end(ctx)
+    if args.graph:
+        if streamed is not None:
+            log("bench.py: --graph and --streamed do not combine (the transfers use a second stream)")
+            sys.exit(2)
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                step()
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
+        # stage times of one eager pass, for the breakdown only
+        B.moe_profile_begin(ctx, 3)
+        for _ in range(3):
+            step()
+        torch.cuda.synchronize()
+        stage_ms, launches, calls = B.moe_profile_end(ctx)
+    else:
+        B.moe_profile_begin(ctx, args.steps)
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
+        stage_ms, launches, calls = B.moe_profile_end(ctx)
     counts = torch.empty(cfg.E, dtype=torch.int32, device="cuda")
     B.moe_last_routing(ctx, min(T, args.micro) if args.micro > 0 else T, counts=counts)
     torch.cuda.synchronize()
@@ -289,7 +315,7 @@ def main():
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": cfg.name, "T": T, "d_model": cfg.d_model, "d_ff": cfg.d_ff, "E": cfg.E,
-                   "k": cfg.k, "micro_tokens": args.micro or None,
+                   "k": cfg.k, "micro_tokens": args.micro or None, "hip_graph": bool(args.graph),
                    "rows_per_expert_last_call": counts.cpu().tolist()},
         "expert_gemm_TFLOP/s": gemm_tflops,
         "expert_gemm_frac_of_bf16_peak": gemm_tflops / PEAK_BF16_TFLOPS,

@@ -20,6 +20,10 @@
  *   - Return value: MOE_OK or a negative moe_status. Arguments are checked on the host
  *     before anything is enqueued; on an argument error nothing has been launched.
  *   - T = 0 is legal and a no-op. An expert that receives no row is legal.
+ *   - The calls that take `stream` only enqueue kernels (and, for moe_last_routing, device
+ *     copies) on it: after one ordinary call of the same kind and shape (the first launch of a
+ *     kernel sets its attributes) they may be recorded into a HIP graph and replayed, except
+ *     moe_layer_forward_streamed (second stream) and calls made while profiling is armed.
  *   - A context is bound to one device and must be used from one stream at a time: its
  *     workspace is shared by consecutive calls.
  *   - Supported shapes: d_model a multiple of 512, d_ff a multiple of 128,

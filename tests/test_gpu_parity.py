@@ -478,6 +478,40 @@ def test_layer_mixtral8x22b_coalesced_vs_microbatched(experts_8x22b):
     ctx.close()
 
 
+def test_layer_replays_from_a_hip_graph():
+    """The layer call only enqueues kernels (no allocation, no memset, no host synchronisation),
+    so it can be captured once and replayed: every replay must give the eager result for the
+    input that is in the captured buffer at that time."""
+    cfg = synth.PRESETS["tiny"]
+    say("layer tiny captured into a HIP graph, three replays with eager work in between")
+    L = synth.make_layer(cfg, "cuda")
+    T = cfg.T
+    ctx = B.MoeContext(T, cfg.d_model, cfg.d_ff, cfg.E, cfg.k)
+    x = L["x"].clone()
+    y = torch.empty((T, cfg.d_model), dtype=torch.bfloat16, device="cuda")
+    args = (L["w_router"], L["bias"], L["W1"], L["W3"], L["W2"], T)
+    B.moe_layer_forward(ctx, x, *args, y)                 # first launches happen outside the capture
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            B.moe_layer_forward(ctx, x, *args, y)
+    gen = torch.Generator(device="cuda").manual_seed(77)
+    for _ in range(3):
+        x.copy_(torch.randn(x.shape, generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16))
+        y.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        got = bits(y).copy()
+        y_eager = torch.empty_like(y)
+        B.moe_layer_forward(ctx, x, *args, y_eager)
+        torch.cuda.synchronize()
+        assert np.array_equal(got, bits(y_eager))
+    del graph
+    ctx.close()
+
+
 def pinned_tail(W, n):
     return W[W.shape[0] - n:].cpu().contiguous().pin_memory()
 
