@@ -10,6 +10,7 @@
 //               (one block; experts across lanes, slices of the segment range side by side)
 //   3. scatter: position = seg_base[g][e] + rank of the id among equal experts in the segment
 // Ids whose expert index is outside [0,E) are dropped (inv_perm = -1).
+// Up to 4096 ids the three steps run in one workgroup (permute_small_kernel).
 #include "common.h"
 
 namespace moe {
@@ -225,6 +226,84 @@ __global__ __launch_bounds__(kBlockWaves* kWave) void scatter_many_kernel(
     }
 }
 
+// All three steps in one workgroup of 16 wavefronts for up to 16 segments (R <= 4096: decode
+// batches), with the per-segment tables in LDS instead of global memory: one launch, not three.
+constexpr int kSmallWaves = 16;
+__global__ __launch_bounds__(kSmallWaves* kWave) void permute_small_kernel(
+    const int32_t* __restrict__ topk_idx, int R, int E, int32_t* __restrict__ counts,
+    int32_t* __restrict__ offsets, int32_t* __restrict__ perm, int32_t* __restrict__ inv_perm) {
+    __shared__ int32_t table[kSmallWaves][kMaxExperts];   // per segment: count, then start position
+    __shared__ int32_t tot[kMaxExperts];
+    __shared__ int32_t off[kMaxExperts + 1];
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int wv = tid / kWave;
+    const int64_t base = static_cast<int64_t>(wv) * kSegIds;
+    volatile int32_t* mine = table[wv];       // read and written across lanes: never cached
+    int my[kRounds];
+    uint64_t same[kRounds];
+    for (int e = lane; e < E; e += kWave) mine[e] = 0;
+#pragma unroll
+    for (int r = 0; r < kRounds; ++r) {
+        const int64_t i = base + r * kWave + lane;
+        my[r] = (i < R) ? topk_idx[i] : -1;
+        if (my[r] < 0 || my[r] >= E) my[r] = -1;
+        same[r] = same_value_lanes(my[r]);
+        if (my[r] >= 0 && (same[r] & lanemask_lt(lane)) == 0) mine[my[r]] += __popcll(same[r]);
+    }
+    __syncthreads();
+    if (tid < E) {                            // segments of one expert, in order
+        int run = 0;
+        for (int g = 0; g < kSmallWaves; ++g) {
+            const int v = table[g][tid];
+            table[g][tid] = run;
+            run += v;
+        }
+        tot[tid] = run;
+    }
+    __syncthreads();
+    if (tid < kWave) {                        // exclusive prefix over the experts, 4 per lane
+        int part[kExpertWords], sum = 0;
+#pragma unroll
+        for (int w = 0; w < kExpertWords; ++w) {
+            const int x = tid * kExpertWords + w;
+            part[w] = x < E ? tot[x] : 0;
+            sum += part[w];
+        }
+        int incl = sum;
+        for (int s = 1; s < kWave; s <<= 1) {
+            const int up = __shfl_up(incl, s, kWave);
+            if (tid >= s) incl += up;
+        }
+        int run = incl - sum;
+#pragma unroll
+        for (int w = 0; w < kExpertWords; ++w) {
+            const int x = tid * kExpertWords + w;
+            if (x < E) off[x] = run;
+            run += part[w];
+        }
+        if (tid == kWave - 1) off[E] = incl;
+    }
+    __syncthreads();
+    if (tid < E) {
+        counts[tid] = tot[tid];
+        offsets[tid] = off[tid];
+    }
+    if (tid == 0) offsets[E] = off[E];
+    for (int e = lane; e < E; e += kWave) mine[e] += off[e];   // start positions of this segment
+#pragma unroll
+    for (int r = 0; r < kRounds; ++r) {
+        const int64_t i = base + r * kWave + lane;
+        int pos = -1;
+        if (my[r] >= 0) pos = mine[my[r]] + __popcll(same[r] & lanemask_lt(lane));
+        if (my[r] >= 0 && (same[r] & lanemask_lt(lane)) == 0) mine[my[r]] = pos + __popcll(same[r]);
+        if (i < R) {
+            inv_perm[i] = pos;
+            if (pos >= 0) perm[pos] = static_cast<int32_t>(i);
+        }
+    }
+}
+
 // One block per permuted row: x_perm[p,:] = x[perm[p] / k, :], 16 bytes per lane per step.
 // Rows at or past *n_grouped (ids dropped for an out-of-range expert index) are zero-filled.
 __global__ __launch_bounds__(256) void gather_kernel(const uint16_t* __restrict__ x,
@@ -252,6 +331,11 @@ size_t permute_scratch_ints(int R_max, int E) {
 int launch_permute(const int32_t* topk_idx, int R, int E, int32_t* counts, int32_t* offsets,
                    int32_t* perm, int32_t* inv_perm, int32_t* scratch, hipStream_t s) {
     const int nseg = (R + kSegIds - 1) / kSegIds;
+    if (nseg <= kSmallWaves) {
+        hipLaunchKernelGGL(permute_small_kernel, dim3(1), dim3(kSmallWaves * kWave), 0, s, topk_idx,
+                           R, E, counts, offsets, perm, inv_perm);
+        return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
+    }
     int32_t* seg_hist = scratch;
     int32_t* seg_base = scratch + static_cast<size_t>(nseg) * E;
     const int blocks = (nseg + kBlockWaves - 1) / kBlockWaves;
