@@ -103,6 +103,7 @@ using GateUpTiny   = Config<32, 128, 64, 1, 2, 7, true>;
 using GateUpTinyS  = Config<32, 128, 64, 1, 2, 7, true, true>;
 using DownTiny     = Config<32, 128, 64, 1, 2, 7, false>;
 using DownTinyS    = Config<32, 128, 64, 1, 2, 7, false, true>;
+using DownTinyNarrowS = Config<32, 64, 64, 1, 2, 11, false, true>;   // more, narrower tiles
 
 }  // namespace
 
@@ -159,6 +160,10 @@ int launch_down(const moe_bf16* H, const int32_t* offsets, int R, int R_hint, in
                 return launch_grouped<DownMidS>(H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
             return launch_grouped<DownMid>(H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
         case 3:
+            // with fewer routed rows than experts only about R experts have a tile: narrower
+            // tiles so that their weights still stream through most compute units
+            if (static_cast<long long>(R_hint < E ? R_hint : E) * (d / 128) < 192 && single_m_tile(R_hint, E, 32))
+                return launch_grouped<DownTinyNarrowS>(H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
             if (d % 128 == 0) {
                 if (single_m_tile(R_hint, E, 32))
                     return launch_grouped<DownTinyS>(H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
