@@ -212,10 +212,11 @@ def main():
         dev_w = [L[m][:cfg.E - n] if n < cfg.E else None for m in ("W1", "W3", "W2")]
         # host-to-device rate of this machine, alone: one expert's three matrices, pinned
         probe = torch.empty(host_w[0][0].numel(), dtype=torch.bfloat16, device="cuda")
+        probe.copy_(host_w[0][0].view(-1), non_blocking=True)       # untimed first touch
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         reps = 0
-        while reps < 3 * n:
+        while reps < 3 * n or reps * probe.numel() * 2 < (2 << 30):  # at least 2 GiB
             for hw in host_w:
                 probe.copy_(hw[reps // 3 % n].view(-1), non_blocking=True)
                 reps += 1

@@ -35,6 +35,7 @@ int launch_route(const moe_bf16* x, const float* w_router, const float* bias, in
 int launch_route_from_logits(const float* logits, int T, int E, int k, int32_t* topk_idx,
                              float* topk_w, hipStream_t s);
 size_t permute_scratch_ints(int R_max, int E);
+int permute_launches(int R);     // kernels that launch_permute enqueues for R ids
 int launch_permute(const int32_t* topk_idx, int R, int E, int32_t* counts, int32_t* offsets,
                    int32_t* perm, int32_t* inv_perm, int32_t* scratch, hipStream_t s);
 int launch_gather(const moe_bf16* x, const int32_t* perm, const int32_t* offsets, int R, int d,

@@ -110,7 +110,7 @@ int forward_chunk(moe_ctx* c, const moe_bf16* x, const float* w_router, const fl
         return launch_route(x, w_router, bias, T, d, E, k, c->topk_idx, c->topk_w, nullptr, c->logits, s);
     });
     if (rc != MOE_OK) return rc;
-    rc = run_stage(c, MOE_STAGE_PERMUTE, 3, s, [&] {
+    rc = run_stage(c, MOE_STAGE_PERMUTE, permute_launches(R), s, [&] {
         return launch_permute(c->topk_idx, R, E, c->counts, c->offsets, c->perm, c->inv_perm,
                               c->scratch, s);
     });
@@ -365,7 +365,7 @@ int moe_layer_forward_streamed(moe_ctx* c, const moe_bf16* x, const float* w_rou
         return launch_route(x, w_router, bias, T, d, E, k, c->topk_idx, c->topk_w, nullptr, c->logits, s);
     });
     if (rc != MOE_OK) return rc;
-    rc = run_stage(c, MOE_STAGE_PERMUTE, 3, s, [&] {
+    rc = run_stage(c, MOE_STAGE_PERMUTE, permute_launches(R), s, [&] {
         return launch_permute(c->topk_idx, R, E, c->counts, c->offsets, c->perm, c->inv_perm,
                               c->scratch, s);
     });

@@ -328,6 +328,8 @@ size_t permute_scratch_ints(int R_max, int E) {
     return 2 * nseg * static_cast<size_t>(E);           // seg_hist + seg_base
 }
 
+int permute_launches(int R) { return (R + kSegIds - 1) / kSegIds <= kSmallWaves ? 1 : 3; }
+
 int launch_permute(const int32_t* topk_idx, int R, int E, int32_t* counts, int32_t* offsets,
                    int32_t* perm, int32_t* inv_perm, int32_t* scratch, hipStream_t s) {
     const int nseg = (R + kSegIds - 1) / kSegIds;
