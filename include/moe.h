@@ -25,7 +25,8 @@
  *     kernel sets its attributes) they may be recorded into a HIP graph and replayed, except
  *     moe_layer_forward_streamed (second stream) and calls made while profiling is armed.
  *   - A context is bound to one device and must be used from one stream at a time: its
- *     workspace is shared by consecutive calls.
+ *     workspace is shared by consecutive calls. That device must be the calling thread's
+ *     current device when a call that takes `stream` is made (MOE_ERR_INVALID_ARG otherwise).
  *   - Supported shapes: d_model a multiple of 512, d_ff a multiple of 128,
  *     1 <= k <= min(E, 64), E <= 256, 0 <= T <= T_max, T_max * k < 2^31 (row offsets into the
  *     tensors are 64-bit inside the kernels). Anything else is MOE_ERR_UNSUPPORTED_SHAPE.

@@ -55,6 +55,12 @@ bool shape_ok(const moe_shape* s) {
 
 size_t align_up(size_t v) { return (v + 255) & ~static_cast<size_t>(255); }
 
+// Kernels launch on the calling thread's current device: it must be the context's.
+bool on_own_device(const moe_ctx* c) {
+    int dev = -1;
+    return hipGetDevice(&dev) == hipSuccess && dev == c->device;
+}
+
 struct Layout {
     size_t topk_idx, topk_w, counts, offsets, perm, inv_perm, scratch, logits, x_perm, H, y_perm, total;
 };
@@ -143,18 +149,32 @@ int ensure_streaming(moe_ctx* c) {
     if (c->copy_stream) return MOE_OK;
     const size_t bytes = static_cast<size_t>(3) * c->shape.d_model * c->shape.d_ff * sizeof(moe_bf16);
     void* p = nullptr;
+    hipStream_t st = nullptr;
+    hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
+    int made = 0;
+    int rc = MOE_OK;
     if (hipMalloc(&p, 2 * bytes) != hipSuccess) {
         (void)hipGetLastError();
         return MOE_ERR_WORKSPACE;
     }
+    for (; made < 4; ++made)
+        if (hipEventCreateWithFlags(&ev[made], hipEventDisableTiming) != hipSuccess) { rc = MOE_ERR_HIP; break; }
+    if (rc == MOE_OK && hipStreamCreateWithFlags(&st, hipStreamNonBlocking) != hipSuccess)   // default priority
+        rc = MOE_ERR_HIP;
+    if (rc != MOE_OK) {                       // leave the context as it was
+        for (int i = 0; i < made; ++i) (void)hipEventDestroy(ev[i]);
+        (void)hipFree(p);
+        (void)hipGetLastError();
+        return rc;
+    }
     c->slot[0] = static_cast<unsigned char*>(p);
     c->slot[1] = c->slot[0] + bytes;
     for (int i = 0; i < 2; ++i) {
-        MOE_HIP_TRY(hipEventCreateWithFlags(&c->ready[i], hipEventDisableTiming));
-        MOE_HIP_TRY(hipEventCreateWithFlags(&c->freed[i], hipEventDisableTiming));
+        c->ready[i] = ev[i];
+        c->freed[i] = ev[2 + i];
         c->freed_valid[i] = false;
     }
-    MOE_HIP_TRY(hipStreamCreateWithFlags(&c->copy_stream, hipStreamNonBlocking));   // default priority
+    c->copy_stream = st;
     return MOE_OK;
 }
 
@@ -241,6 +261,7 @@ int moe_destroy(moe_ctx* c) {
 int moe_route(moe_ctx* c, const moe_bf16* x, const float* w_router, const float* bias, int32_t T,
               int32_t* topk_idx, float* topk_w, float* logits_out, void* stream) {
     if (!c || T < 0 || T > c->shape.T_max) return MOE_ERR_INVALID_ARG;
+    if (!on_own_device(c)) return MOE_ERR_INVALID_ARG;
     if (T == 0) return MOE_OK;
     if (!x || !w_router || !topk_idx || !topk_w) return MOE_ERR_INVALID_ARG;
     return launch_route(x, w_router, bias, T, c->shape.d_model, c->shape.E, c->shape.k, topk_idx,
@@ -250,6 +271,7 @@ int moe_route(moe_ctx* c, const moe_bf16* x, const float* w_router, const float*
 int moe_route_from_logits(moe_ctx* c, const float* logits, int32_t T, int32_t* topk_idx,
                           float* topk_w, void* stream) {
     if (!c || T < 0 || T > c->shape.T_max) return MOE_ERR_INVALID_ARG;
+    if (!on_own_device(c)) return MOE_ERR_INVALID_ARG;
     if (T == 0) return MOE_OK;
     if (!logits || !topk_idx || !topk_w) return MOE_ERR_INVALID_ARG;
     return launch_route_from_logits(logits, T, c->shape.E, c->shape.k, topk_idx, topk_w,
@@ -260,6 +282,7 @@ int moe_permute(moe_ctx* c, const int32_t* topk_idx, int32_t T, int32_t* counts,
                 int32_t* perm, int32_t* inv_perm, const moe_bf16* x, moe_bf16* x_perm,
                 void* stream) {
     if (!c || T < 0 || T > c->shape.T_max) return MOE_ERR_INVALID_ARG;
+    if (!on_own_device(c)) return MOE_ERR_INVALID_ARG;
     if (!counts || !offsets) return MOE_ERR_INVALID_ARG;
     if (T > 0 && (!topk_idx || !perm || !inv_perm)) return MOE_ERR_INVALID_ARG;
     if ((x == nullptr) != (x_perm == nullptr)) return MOE_ERR_INVALID_ARG;
@@ -277,6 +300,7 @@ int moe_expert_ffn(moe_ctx* c, const moe_bf16* x_perm, const int32_t* offsets, i
                    void* stream) {
     if (!c || R < 0 || static_cast<long long>(R) > static_cast<long long>(c->shape.T_max) * c->shape.k)
         return MOE_ERR_INVALID_ARG;
+    if (!on_own_device(c)) return MOE_ERR_INVALID_ARG;
     if (R == 0) return MOE_OK;
     if (!x_perm || !offsets || !W1 || !W3 || !W2 || !y_perm) return MOE_ERR_INVALID_ARG;
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -289,6 +313,7 @@ int moe_expert_ffn(moe_ctx* c, const moe_bf16* x_perm, const int32_t* offsets, i
 int moe_combine(moe_ctx* c, const moe_bf16* y_perm, const int32_t* inv_perm, const float* topk_w,
                 int32_t T, moe_bf16* y, void* stream) {
     if (!c || T < 0 || T > c->shape.T_max) return MOE_ERR_INVALID_ARG;
+    if (!on_own_device(c)) return MOE_ERR_INVALID_ARG;
     if (T == 0) return MOE_OK;
     if (!y_perm || !inv_perm || !topk_w || !y) return MOE_ERR_INVALID_ARG;
     return launch_combine(y_perm, inv_perm, topk_w, T, c->shape.d_model, c->shape.k, y,
@@ -299,6 +324,7 @@ int moe_layer_forward(moe_ctx* c, const moe_bf16* x, const float* w_router, cons
                       const moe_bf16* W1, const moe_bf16* W3, const moe_bf16* W2, int32_t T,
                       moe_bf16* y, void* stream) {
     if (!c || T < 0 || T > c->shape.T_max) return MOE_ERR_INVALID_ARG;
+    if (!on_own_device(c)) return MOE_ERR_INVALID_ARG;
     if (T == 0) return MOE_OK;
     if (!x || !w_router || !W1 || !W3 || !W2 || !y) return MOE_ERR_INVALID_ARG;
     if (c->prof_armed) c->prof_calls++;
@@ -310,6 +336,7 @@ int moe_layer_forward_microbatched(moe_ctx* c, const moe_bf16* x, const float* w
                                    const moe_bf16* W2, int32_t T, int32_t micro_tokens,
                                    moe_bf16* y, void* stream) {
     if (!c || T < 0 || T > c->shape.T_max || micro_tokens < 1) return MOE_ERR_INVALID_ARG;
+    if (!on_own_device(c)) return MOE_ERR_INVALID_ARG;
     if (T == 0) return MOE_OK;
     if (!x || !w_router || !W1 || !W3 || !W2 || !y) return MOE_ERR_INVALID_ARG;
     if (c->prof_armed) c->prof_calls++;
@@ -330,6 +357,7 @@ int moe_layer_forward_streamed(moe_ctx* c, const moe_bf16* x, const float* w_rou
                                int32_t n_streamed, int32_t T, moe_bf16* y, void* stream) {
     if (!c || T < 0 || T > c->shape.T_max || n_streamed < 0 || n_streamed > c->shape.E)
         return MOE_ERR_INVALID_ARG;
+    if (!on_own_device(c)) return MOE_ERR_INVALID_ARG;
     if (T == 0) return MOE_OK;
     const moe_shape& sh = c->shape;
     const int d = sh.d_model, f = sh.d_ff, E = sh.E, k = sh.k, R = T * k;
@@ -399,6 +427,7 @@ int moe_layer_forward_streamed(moe_ctx* c, const moe_bf16* x, const float* w_rou
 int moe_last_routing(moe_ctx* c, int32_t T, int32_t* topk_idx, float* topk_w, int32_t* counts,
                      int32_t* offsets, int32_t* perm, int32_t* inv_perm, void* stream) {
     if (!c || T < 0 || T > c->shape.T_max) return MOE_ERR_INVALID_ARG;
+    if (!on_own_device(c)) return MOE_ERR_INVALID_ARG;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const size_t R = static_cast<size_t>(T) * c->shape.k, E = static_cast<size_t>(c->shape.E);
     auto copy = [&](void* dst, const void* src, size_t bytes) -> int {
