@@ -154,7 +154,8 @@ int moe_layer_forward_microbatched(moe_ctx* ctx, const moe_bf16* x, const float*
 /* moe_layer_forward with the weights of the last `n_streamed` experts kept in pinned host memory
  * and moved to the GPU while the other experts compute (the expert group that the paper's
  * Section 4.1.1 moves over PCIe: Eq. 7 prices the transfer at D_Y per moved expert over the PCIe
- * bandwidth, and transfer and computation overlap). Experts [0, E - n_streamed) are resident:
+ * bandwidth; the paper's latency model adds that to the computation time, Eq. 3, whereas this
+ * call overlaps the two). Experts [0, E - n_streamed) are resident:
  * W1, W3 [E - n_streamed, d_ff, d_model], W2 [E - n_streamed, d_model, d_ff] in device memory
  * (ignored, may be NULL, when n_streamed == E). Experts [E - n_streamed, E) are read from
  * W1_host, W3_host [n_streamed, d_ff, d_model], W2_host [n_streamed, d_model, d_ff]: HOST pointers
