@@ -227,7 +227,10 @@ int moe_estimate_expert_stage(const moe_shape* shape, const int32_t* rows, int32
  * average rows per expert. Adding 16 to any of these makes the medium and small tiles load the
  * weights as ordinary (cached) lines, adding 32 as non-temporal ones; without either the library
  * picks non-temporal loads when about every expert has a single row tile (decode), where each
- * weight byte is used once. Every setting produces identical bits (same accumulation chain per
+ * weight byte is used once. Adding 64 makes moe_layer_forward and its micro-batched form write
+ * the gathered rows x_perm to the workspace and run the gate/up GEMM on them (the path taken by
+ * itself when T*d_model*2 bytes do not fit 32 bits) instead of reading token rows through the
+ * permutation. Every setting produces identical bits (same accumulation chain per
  * output element); only speed differs. Returns MOE_ERR_INVALID_ARG for other values. */
 int moe_set_gemm_config(int config);
 

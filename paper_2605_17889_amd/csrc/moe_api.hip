@@ -44,6 +44,8 @@ namespace {
 
 using namespace moe;
 
+bool g_materialise_gather = false;   // testing knob: take the unfused path at any size
+
 bool shape_ok(const moe_shape* s) {
     if (!s) return false;
     if (s->T_max < 0 || s->d_model <= 0 || s->d_ff <= 0 || s->E <= 0 || s->k <= 0) return false;
@@ -123,7 +125,8 @@ int forward_chunk(moe_ctx* c, const moe_bf16* x, const float* w_router, const fl
     if (rc != MOE_OK) return rc;
     // The row gather x -> x_perm is fused into the gate/up kernel's operand loads (it reads
     // token row perm[p] / k directly) whenever a token row's byte offset fits 32 bits.
-    const bool fuse_gather = static_cast<unsigned long long>(T) * d * 2ull < (1ull << 32);
+    const bool fuse_gather =
+        !g_materialise_gather && static_cast<unsigned long long>(T) * d * 2ull < (1ull << 32);
     if (!fuse_gather) {
         rc = run_stage(c, MOE_STAGE_GATHER, 1, s, [&] {
             return launch_gather(x, c->perm, c->offsets, R, d, k, E, c->x_perm, s);
@@ -479,12 +482,17 @@ int moe_profile_end(moe_ctx* c, double* stage_ms, int64_t* stage_launches, int32
 
 /* Tuning/testing knob: force the expert-GEMM tile configuration (0 large, 1 medium, 2 small,
  * 3 tiny rows-per-expert), or -1 for the automatic choice; +16 never loads weights as non-temporal,
- * +32 always does (medium and small tiles). All settings give identical bits. */
+ * +32 always does (medium and small tiles); +64 makes the layer calls write the gathered rows
+ * to the workspace instead of reading them through the permutation. All settings give
+ * identical bits. */
 int moe_set_gemm_config(int config) {
     int stream_mode = -1;
+    bool materialise = false;
+    if (config >= 63) { materialise = true; config -= 64; }
     if (config >= 31) { stream_mode = 1; config -= 32; }
     else if (config >= 15) { stream_mode = 0; config -= 16; }
     if (config < -1 || config > 3) return MOE_ERR_INVALID_ARG;
+    g_materialise_gather = materialise;
     moe::set_gemm_config(config, stream_mode);
     return MOE_OK;
 }

@@ -83,7 +83,8 @@ def test_null_arguments_are_rejected_before_any_gpu_work(lib):
                                           1, 4, None, None) == -1
     assert lib.moe_set_gemm_config(9) == -1
     assert lib.moe_set_gemm_config(4 + 32) == -1
-    for ok in (0, 3, 1 + 16, -1 + 32, -1):
+    assert lib.moe_set_gemm_config(4 + 64) == -1
+    for ok in (0, 3, 1 + 16, -1 + 32, -1 + 64, 2 + 32 + 64, -1):
         assert lib.moe_set_gemm_config(ok) == 0
 
 

@@ -463,6 +463,24 @@ def test_layer_mixtral8x22b_prefill(experts_8x22b):
     ctx.close()
 
 
+def test_layer_mixtral8x22b_large_batch(experts_8x22b):
+    """T = 65536: the intermediate H is 4.3 GB, past 32-bit byte offsets."""
+    import dataclasses
+    cfg = dataclasses.replace(synth.PRESETS["mixtral8x22b_prefill"], T=65536, seed=12)
+    say("layer 8x22B, T=65536 (H beyond 4 GiB)")
+    L, Hh = layer_8x22b(cfg, experts_8x22b)
+    y, ctx = run_layer(cfg, L)
+    routing = fetch_routing(ctx, cfg.T)
+    _, o_ref, p_ref = check_routing_exact(cfg, Hh, routing, cfg.T)
+    say(f"    rows per expert {routing['counts'].tolist()}")
+    tokens = sample_tokens(cfg, o_ref, p_ref, 4, 3)
+    want, _, _ = ref.layer_tokens(Hh["x"], Hh["w_router"], None, Hh["W1"], Hh["W3"], Hh["W2"], cfg.k, tokens)
+    assert_close_ffn(bits(y)[tokens], want, f"8x22B T=65536 ({tokens.size} tokens)")
+    ctx.close()
+    del L, y
+    torch.cuda.empty_cache()
+
+
 def test_layer_mixtral8x22b_coalesced_vs_microbatched(experts_8x22b):
     cfg = synth.PRESETS["mixtral8x22b_coalesce"]
     say(f"layer 8x22B T={cfg.T}: coalesced vs {cfg.T // cfg.micro_tokens} micro-batches of {cfg.micro_tokens}")
@@ -475,6 +493,25 @@ def test_layer_mixtral8x22b_coalesced_vs_microbatched(experts_8x22b):
     tokens = sample_tokens(cfg, o_ref, p_ref, 4, 3)
     want, _, _ = ref.layer_tokens(Hh["x"], Hh["w_router"], None, Hh["W1"], Hh["W3"], Hh["W2"], cfg.k, tokens)
     assert_close_ffn(bits(y)[tokens], want, f"8x22B coalesced ({tokens.size} tokens)")
+    ctx.close()
+
+
+@pytest.mark.parametrize("preset", ["tiny", "mixtral8x7b_decode"])
+def test_layer_with_materialised_gather_bitwise(preset):
+    """The unfused path (gathered rows written to the workspace, taken by itself for batches
+    beyond 32-bit row offsets) gives the bits of the fused one."""
+    cfg = synth.PRESETS[preset]
+    say(f"layer {preset}: gather materialised vs fused into the gate/up loads")
+    L = synth.make_layer(cfg, "cuda")
+    y_fused, ctx = run_layer(cfg, L)
+    B.moe_set_gemm_config(-1 + 64)
+    try:
+        y_plain, _ = run_layer(cfg, L, ctx=ctx)
+        y_micro, _ = run_layer(cfg, L, micro=100, ctx=ctx)
+    finally:
+        B.moe_set_gemm_config(-1)
+    assert np.array_equal(bits(y_plain), bits(y_fused))
+    assert np.array_equal(bits(y_micro), bits(y_fused))
     ctx.close()
 
 
