@@ -178,6 +178,9 @@ def test_route_from_logits_many_experts_ties_and_order():
     (1, 8, 2, 0, False), (37, 8, 2, 1, True), (256, 8, 2, 2, False), (1000, 64, 6, 3, False),
     (4096, 8, 2, 4, True), (777, 3, 3, 5, False), (16384, 8, 2, 6, False), (129, 40, 1, 7, True),
     (5000, 128, 8, 8, True), (333, 65, 2, 9, False), (2000, 256, 6, 10, True), (64, 200, 64, 11, False),
+    # around the single-launch limit of 4096 ids, and the multi-launch path at other expert counts
+    (4096, 5, 1, 12, False), (4097, 8, 1, 13, False), (1025, 8, 4, 14, True), (3000, 16, 4, 15, False),
+    (2100, 33, 2, 16, True), (70000, 17, 1, 17, False),
 ])
 def test_permute_bit_exact(T, E, k, seed, empty):
     say(f"permute T={T} E={E} k={k} empty={empty}")
