@@ -60,3 +60,28 @@ def expert_stage_estimate(rows, d_model, d_ff, tflops, gbytes_per_s):
     denom = 6.0 * d * f / TF - 2.0 * d / BW
     out["ridge_rows"] = (6.0 * d * f / BW) / denom if denom > 0 else float("inf")
     return out
+
+
+def streamed_expert_stage_estimate(rows, d_model, d_ff, n_moved, tflops, gbytes_per_s,
+                                   pcie_gbytes_per_s, inputs_on_device=True):
+    """Expert stage with n_moved experts' weights brought over PCIe (the paper's EXP_M group).
+
+    rows: list (experts) of routed row counts of the one coalesced batch (m_exp = B).
+      t_load_s     Eq. 7:  (D_X3 + EXP_M * D_Y3) / BW_PCIe, with D_Y3 = 6*d_h*d_e per expert and
+                   D_X3 = 2*rows*d_h over all experts' inputs, left out when they already sit on
+                   the device
+      t_comp_s     Eq. 9 for the GPU with every expert computed there: max(bytes / BW, C / TF)
+      t_sum_s      Eq. 3: T_load + T_comp (no T_store in the expert stage, Eq. 6)
+      t_overlap_s  max(T_load, T_comp): transfer fully hidden behind computation or the reverse
+    """
+    d, f = float(d_model), float(d_ff)
+    pcie = pcie_gbytes_per_s * 1e9
+    if not 0 <= n_moved <= len(rows):
+        raise ValueError("n_moved out of range")
+    moved = n_moved * 6.0 * d * f
+    if not inputs_on_device:
+        moved += sum(2.0 * float(r) * d for r in rows if r > 0)
+    t_load = moved / pcie
+    t_comp = expert_stage_estimate([list(rows)], d_model, d_ff, tflops, gbytes_per_s)["t_stage_s"]
+    return dict(moved_bytes=moved, t_load_s=t_load, t_comp_s=t_comp, t_sum_s=t_load + t_comp,
+                t_overlap_s=max(t_load, t_comp))

@@ -425,3 +425,27 @@ def test_cost_model_benchmark_floors():
     o = est([[64] * 8] * 16, 6144, 16384, 2500.0, 8000.0)
     assert abs(o["t_stage_s"] * 1e3 - 16 * (4.832e9 + 8 * 64 * 6144 * 2) / 8e12 * 1e3) < 1e-3
     assert 9.66 < o["t_stage_s"] * 1e3 < 9.69 and o["memory_bound_instances"] == 128
+
+
+def test_streamed_cost_model_hand_values():
+    """Eq. 7 / Eq. 3 by hand. d_h = 512, d_e = 128: one expert's matrices are 6*512*128 =
+    393 216 B. Two of four experts moved at 1 GB/s: 786 432 B -> 786.432 us. Rows (100, 0, 50,
+    10): inputs 2*160*512 = 163 840 B; with the inputs moved too: 950 272 B -> 950.272 us.
+    Computation at 1 TFLOP/s, 1 GB/s device memory: bytes = 3 experts * 393 216 + 163 840 =
+    1 343 488 B -> 1343.488 us; FLOPs 6*160*512*128 = 62 914 560 -> 62.9 us: memory side."""
+    from oracle import cost_model as cm
+    r = cm.streamed_expert_stage_estimate([100, 0, 50, 10], 512, 128, 2, 1.0, 1.0, 1.0)
+    assert r["moved_bytes"] == 786432.0
+    assert abs(r["t_load_s"] - 786.432e-6) < 1e-12
+    assert abs(r["t_comp_s"] - 1343.488e-6) < 1e-12
+    assert abs(r["t_sum_s"] - (786.432e-6 + 1343.488e-6)) < 1e-12
+    assert abs(r["t_overlap_s"] - 1343.488e-6) < 1e-12
+    r = cm.streamed_expert_stage_estimate([100, 0, 50, 10], 512, 128, 2, 1.0, 1.0, 1.0,
+                                          inputs_on_device=False)
+    assert r["moved_bytes"] == 950272.0 and abs(r["t_load_s"] - 950.272e-6) < 1e-12
+    # nothing moved: the load term vanishes and sum == overlap == computation
+    r = cm.streamed_expert_stage_estimate([100, 0, 50, 10], 512, 128, 0, 1.0, 1.0, 1.0)
+    assert r["t_load_s"] == 0.0 and r["t_sum_s"] == r["t_overlap_s"] == r["t_comp_s"]
+    # fast device, slow link: the transfer is the larger term
+    r = cm.streamed_expert_stage_estimate([2048] * 8, 6144, 16384, 2, 2500.0, 8000.0, 57.0)
+    assert abs(r["t_load_s"] - 2 * 6 * 6144 * 16384 / 57e9) < 1e-9 and r["t_overlap_s"] == r["t_load_s"]
