@@ -327,6 +327,12 @@ def main():
     }
     if streamed is not None:
         streamed["measured_over_estimate"] = ms_per_step / streamed["estimate_ms"]
+        # the same terms from the roofline model alone (Eq. 7, Eq. 9, Eq. 3) at the rates this
+        # library sustains and the host-to-device rate measured above
+        m = B.moe_estimate_streamed_stage(cfg.d_model, cfg.d_ff, counts.cpu().tolist(), args.streamed,
+                                          SUSTAINED_TFLOPS, SUSTAINED_GBS, streamed["h2d_GB/s_measured"])
+        streamed["model"] = {"t_load_ms": m["t_load_s"] * 1e3, "t_comp_ms": m["t_comp_s"] * 1e3,
+                             "t_sum_ms": m["t_sum_s"] * 1e3, "t_overlap_ms": m["t_overlap_s"] * 1e3}
         out["streamed"] = streamed
     if not args.no_cpu_baseline:
         log("[bench] timing the CPU oracle on a token sample")

@@ -222,6 +222,25 @@ typedef struct {
 int moe_estimate_expert_stage(const moe_shape* shape, const int32_t* rows, int32_t micro_batches,
                               const moe_machine* machine, moe_expert_estimate* out);
 
+/* Roofline estimate of the expert stage when the weights of `n_moved` experts come over PCIe
+ * (paper Section 4.1.1): Eq. 7 prices the transfer, T_load = (D_X3 + EXP_M * D_Y3) / BW_PCIe
+ * with D_Y3 = 6*d_h*d_e bytes per moved expert and D_X3 = 2*rows*d_h the stage's inputs (left out
+ * when inputs_on_device is non-zero); the computation is the Eq. 9 latency of the GPU with every
+ * expert computed there (t_stage_s of moe_estimate_expert_stage for one coalesced batch); Eq. 3
+ * adds the two, and their maximum is what complete overlap would give. Host arithmetic only.
+ * rows: HOST array [E] of routed row counts; 0 <= n_moved <= E; rates > 0. */
+typedef struct {
+    double moved_bytes;             /* bytes over PCIe */
+    double t_load_s;                /* Eq. 7 */
+    double t_comp_s;                /* Eq. 9, all experts on the GPU */
+    double t_sum_s;                 /* Eq. 3: t_load_s + t_comp_s */
+    double t_overlap_s;             /* max(t_load_s, t_comp_s) */
+} moe_streamed_estimate;
+
+int moe_estimate_streamed_stage(const moe_shape* shape, const int32_t* rows, int32_t n_moved,
+                                const moe_machine* machine, double pcie_gbytes_per_s,
+                                int32_t inputs_on_device, moe_streamed_estimate* out);
+
 /* Tuning / testing knob, process-wide: force the expert-GEMM tile configuration
  * (0 = large, 1 = medium, 2 = small, 3 = tiny rows-per-expert tile) or -1 for the automatic choice by
  * average rows per expert. Adding 16 to any of these makes the medium and small tiles load the

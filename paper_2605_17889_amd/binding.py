@@ -23,6 +23,7 @@ EXPORTS = (
     "moe_route_from_logits", "moe_permute", "moe_expert_ffn", "moe_combine", "moe_layer_forward",
     "moe_layer_forward_microbatched", "moe_last_routing", "moe_profile_begin", "moe_profile_end",
     "moe_set_gemm_config", "moe_estimate_expert_stage", "moe_layer_forward_streamed",
+    "moe_estimate_streamed_stage",
 )
 
 
@@ -41,6 +42,11 @@ class MoeExpertEstimate(C.Structure):
                 ("operand_bytes", C.c_double), ("intermediate_bytes", C.c_double),
                 ("t_stage_s", C.c_double), ("t_per_expert_s", C.c_double),
                 ("t_kernels_s", C.c_double), ("ridge_rows", C.c_double)]
+
+
+class MoeStreamedEstimate(C.Structure):
+    _fields_ = [("moved_bytes", C.c_double), ("t_load_s", C.c_double), ("t_comp_s", C.c_double),
+                ("t_sum_s", C.c_double), ("t_overlap_s", C.c_double)]
 
 
 class MoeError(RuntimeError):
@@ -243,6 +249,22 @@ def moe_estimate_expert_stage(d_model: int, d_ff: int, rows, tflops: float, gbyt
                                            C.byref(machine), C.byref(out)),
            "moe_estimate_expert_stage")
     return {name: getattr(out, name) for name, _ in MoeExpertEstimate._fields_}
+
+
+def moe_estimate_streamed_stage(d_model: int, d_ff: int, rows, n_moved: int, tflops: float,
+                                gbytes_per_s: float, pcie_gbytes_per_s: float,
+                                inputs_on_device: bool = True) -> dict:
+    """rows: host sequence [E] of routed row counts of one coalesced batch. Host arithmetic only."""
+    E = len(rows)
+    flat = (C.c_int32 * max(1, E))(*[int(v) for v in rows])
+    shape = MoeShape(0, d_model, d_ff, max(E, 1), 1)
+    mach = MoeMachine(tflops, gbytes_per_s)
+    out = MoeStreamedEstimate()
+    _check(lib().moe_estimate_streamed_stage(C.byref(shape), flat, C.c_int32(n_moved), C.byref(mach),
+                                             C.c_double(pcie_gbytes_per_s),
+                                             C.c_int32(1 if inputs_on_device else 0), C.byref(out)),
+           "moe_estimate_streamed_stage")
+    return {n: getattr(out, n) for n, _ in MoeStreamedEstimate._fields_}
 
 
 def moe_set_gemm_config(config: int):

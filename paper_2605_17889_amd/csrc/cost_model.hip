@@ -56,3 +56,29 @@ extern "C" int moe_estimate_expert_stage(const moe_shape* shape, const int32_t* 
     *out = e;
     return MOE_OK;
 }
+
+// Section 4.1.1 with a group of experts moved over PCIe: the load term of Eq. 7 next to the
+// computation term of Eq. 9 (GPU side, every expert computed there); Eq. 3 sums them.
+extern "C" int moe_estimate_streamed_stage(const moe_shape* shape, const int32_t* rows,
+                                           int32_t n_moved, const moe_machine* machine,
+                                           double pcie_gbytes_per_s, int32_t inputs_on_device,
+                                           moe_streamed_estimate* out) {
+    if (!shape || !rows || !machine || !out) return MOE_ERR_INVALID_ARG;
+    if (shape->d_model <= 0 || shape->d_ff <= 0 || shape->E <= 0) return MOE_ERR_INVALID_ARG;
+    if (n_moved < 0 || n_moved > shape->E || !(pcie_gbytes_per_s > 0.0)) return MOE_ERR_INVALID_ARG;
+    moe_expert_estimate stage;
+    const int rc = moe_estimate_expert_stage(shape, rows, 1, machine, &stage);
+    if (rc != MOE_OK) return rc;
+    const double dh = shape->d_model, de = shape->d_ff;
+    double over_link = 6.0 * dh * de * n_moved;                 // EXP_M * D_Y3
+    if (!inputs_on_device)
+        for (int32_t x = 0; x < shape->E; ++x) over_link += 2.0 * dh * rows[x];   // D_X3
+    moe_streamed_estimate e;
+    e.moved_bytes = over_link;
+    e.t_load_s = over_link / (pcie_gbytes_per_s * 1e9);
+    e.t_comp_s = stage.t_stage_s;
+    e.t_sum_s = e.t_load_s + e.t_comp_s;
+    e.t_overlap_s = e.t_load_s > e.t_comp_s ? e.t_load_s : e.t_comp_s;
+    *out = e;
+    return MOE_OK;
+}

@@ -84,3 +84,47 @@ def test_argument_errors():
     empty = B.moe_estimate_expert_stage(6144, 16384, [], 2500.0, 8000.0)
     assert empty["t_stage_s"] == 0.0 and empty["micro_batches"] == 0
     assert math.isfinite(empty["ridge_rows"])
+
+
+# ------------------------------------------------------------------ experts moved over PCIe
+def test_streamed_estimate_matches_oracle_and_invariants():
+    """moe_estimate_streamed_stage against the oracle's Eq. 7 / Eq. 3 arithmetic, and properties:
+    the load term grows by exactly one expert's matrices per moved expert, the sum is at least
+    the overlap, and the two agree when nothing moves."""
+    from oracle.cost_model import streamed_expert_stage_estimate as oracle_streamed
+    rng = np.random.default_rng(11)
+    for _ in range(40):
+        E = int(rng.integers(1, 130))
+        d, f = int(rng.integers(1, 64)) * 128, int(rng.integers(1, 64)) * 128
+        rows = (rng.integers(0, 3000, size=E) * (rng.random(E) < 0.8)).astype(int).tolist()
+        tf, bw, pcie = float(rng.uniform(10, 3000)), float(rng.uniform(100, 9000)), float(rng.uniform(5, 120))
+        n = int(rng.integers(0, E + 1))
+        on_dev = bool(rng.integers(0, 2))
+        got = B.moe_estimate_streamed_stage(d, f, rows, n, tf, bw, pcie, on_dev)
+        want = oracle_streamed(rows, d, f, n, tf, bw, pcie, on_dev)
+        for name in ("moved_bytes", "t_load_s", "t_comp_s", "t_sum_s", "t_overlap_s"):
+            assert close(got[name], want[name]), name
+        assert got["t_sum_s"] >= got["t_overlap_s"] >= max(got["t_load_s"], got["t_comp_s"]) * (1 - 1e-12)
+        if n < E:
+            more = B.moe_estimate_streamed_stage(d, f, rows, n + 1, tf, bw, pcie, on_dev)
+            assert close(more["moved_bytes"] - got["moved_bytes"], 6.0 * d * f)
+            assert close(more["t_comp_s"], got["t_comp_s"])
+    none = B.moe_estimate_streamed_stage(512, 128, [5, 0, 9], 0, 100.0, 100.0, 10.0, True)
+    assert none["t_load_s"] == 0.0 and none["t_sum_s"] == none["t_overlap_s"] == none["t_comp_s"]
+
+
+def test_streamed_estimate_argument_errors():
+    import ctypes as C
+    L = B.lib()
+    shape = B.MoeShape(0, 512, 128, 4, 1)
+    mach = B.MoeMachine(100.0, 100.0)
+    rows = (C.c_int32 * 4)(1, 2, 3, 4)
+    out = B.MoeStreamedEstimate()
+    ok = lambda *a: L.moe_estimate_streamed_stage(*a)
+    assert ok(C.byref(shape), rows, 2, C.byref(mach), C.c_double(10.0), 1, C.byref(out)) == 0
+    assert ok(None, rows, 2, C.byref(mach), C.c_double(10.0), 1, C.byref(out)) == -1
+    assert ok(C.byref(shape), None, 2, C.byref(mach), C.c_double(10.0), 1, C.byref(out)) == -1
+    assert ok(C.byref(shape), rows, 5, C.byref(mach), C.c_double(10.0), 1, C.byref(out)) == -1
+    assert ok(C.byref(shape), rows, -1, C.byref(mach), C.c_double(10.0), 1, C.byref(out)) == -1
+    assert ok(C.byref(shape), rows, 2, C.byref(mach), C.c_double(0.0), 1, C.byref(out)) == -1
+    assert ok(C.byref(shape), rows, 2, C.byref(mach), C.c_double(10.0), 1, None) == -1
