@@ -118,8 +118,22 @@ int moe_permute(moe_ctx* ctx, const int32_t* topk_idx, int32_t T, int32_t* count
                 int32_t* offsets, int32_t* perm, int32_t* inv_perm, const moe_bf16* x,
                 moe_bf16* x_perm, void* stream);
 
-/* Grouped SwiGLU expert FFN over rows already grouped by expert (paper Table 1 row 3,
- * "gated FFN execution per expert"): for offsets[e] <= p < offsets[e+1],
+/* moe_permute's grouping for callers that cannot allocate device memory or create a context
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): no
+ * moe_ctx, no allocation of any kind. The segment tables that moe_permute keeps in the context
+ * workspace live in a static device array of the library instead (1 MiB per GPU, held until the
+ * process ends), so the size is bounded: ceil(T*k / 256) * E <= 65536 (e.g. T*k <= 2,097,152 ids
+ * at E = 8, 65,536 ids at E = 256); larger inputs return MOE_ERR_UNSUPPORTED_SHAPE. Same outputs
+ * as moe_permute bit for bit (same kernels); no row gather. 1 <= k <= min(E, 64), E <= 256.
+ * All calls on one GPU share that GPU's array: two calls whose work overlaps in time on one GPU
+ * (different streams, or different threads) race; calls on one stream are ordered and safe.
+ * The first call on a device looks up the array's address (no allocation); the calling thread's
+ * current device is the one used. */
+int moe_permute_static(const int32_t* topk_idx, int32_t T, int32_t k, int32_t E, int32_t* counts,
+                       int32_t* offsets, int32_t* perm, int32_t* inv_perm, void* stream);
+
+/* Grouped SwiGLU expert FFN over rows already grouped by expert (the gated feed-forward network
+ * of one expert, paper Section 4.1 and Table 1 row 3): for offsets[e] <= p < offsets[e+1],
  *   y_perm[p,:] = W2_e ( SiLU(W1_e x_perm[p,:]) (.) W3_e x_perm[p,:] ).
  * bf16 operands, fp32 accumulation on the matrix cores, the intermediate H and y_perm
  * rounded to bf16 (nearest even). R = number of rows = offsets[E] (R <= T_max*k).

@@ -23,7 +23,7 @@ EXPORTS = (
     "moe_route_from_logits", "moe_permute", "moe_expert_ffn", "moe_combine", "moe_layer_forward",
     "moe_layer_forward_microbatched", "moe_last_routing", "moe_profile_begin", "moe_profile_end",
     "moe_set_gemm_config", "moe_estimate_expert_stage", "moe_layer_forward_streamed",
-    "moe_estimate_streamed_stage",
+    "moe_estimate_streamed_stage", "moe_permute_static",
 )
 
 
@@ -161,6 +161,15 @@ def moe_permute(ctx: MoeContext, topk_idx, T, counts, offsets, perm, inv_perm, x
                              _ptr(perm, torch.int32, "perm"), _ptr(inv_perm, torch.int32, "inv_perm"),
                              _ptr(x, torch.bfloat16, "x"), _ptr(x_perm, torch.bfloat16, "x_perm"),
                              _stream(stream)), "moe_permute")
+
+
+def moe_permute_static(topk_idx, T, k, E, counts, offsets, perm, inv_perm, stream=None):
+    """The grouping of moe_permute without a context and without any allocation."""
+    _check(lib().moe_permute_static(_ptr(topk_idx, torch.int32, "topk_idx"), C.c_int32(T), C.c_int32(k),
+                                    C.c_int32(E), _ptr(counts, torch.int32, "counts"),
+                                    _ptr(offsets, torch.int32, "offsets"), _ptr(perm, torch.int32, "perm"),
+                                    _ptr(inv_perm, torch.int32, "inv_perm"), _stream(stream)),
+           "moe_permute_static")
 
 
 def moe_expert_ffn(ctx: MoeContext, x_perm, offsets, R, W1, W3, W2, y_perm, stream=None):

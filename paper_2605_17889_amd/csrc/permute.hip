@@ -11,7 +11,14 @@
 //   3. scatter: position = seg_base[g][e] + rank of the id among equal experts in the segment
 // Ids whose expert index is outside [0,E) are dropped (inv_perm = -1).
 // Up to 4096 ids the three steps run in one workgroup (permute_small_kernel).
+#include <mutex>
+
 #include "common.h"
+
+// Segment tables of moe_permute_static(): device memory that exists from load time, so that the
+// call allocates nothing. 2 * kStaticTableInts ints (histograms, then start positions).
+constexpr size_t kStaticTableInts = 65536;
+static __device__ __align__(256) int32_t scratch[2 * kStaticTableInts];
 
 namespace moe {
 namespace {
@@ -331,15 +338,15 @@ size_t permute_scratch_ints(int R_max, int E) {
 int permute_launches(int R) { return (R + kSegIds - 1) / kSegIds <= kSmallWaves ? 1 : 3; }
 
 int launch_permute(const int32_t* topk_idx, int R, int E, int32_t* counts, int32_t* offsets,
-                   int32_t* perm, int32_t* inv_perm, int32_t* scratch, hipStream_t s) {
+                   int32_t* perm, int32_t* inv_perm, int32_t* seg_tables, hipStream_t s) {
     const int nseg = (R + kSegIds - 1) / kSegIds;
     if (nseg <= kSmallWaves) {
         hipLaunchKernelGGL(permute_small_kernel, dim3(1), dim3(kSmallWaves * kWave), 0, s, topk_idx,
                            R, E, counts, offsets, perm, inv_perm);
         return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
     }
-    int32_t* seg_hist = scratch;
-    int32_t* seg_base = scratch + static_cast<size_t>(nseg) * E;
+    int32_t* seg_hist = seg_tables;
+    int32_t* seg_base = seg_tables + static_cast<size_t>(nseg) * E;
     const int blocks = (nseg + kBlockWaves - 1) / kBlockWaves;
     const bool many = E > 16;            // one ballot per expert below, 9 per round above
     if (nseg > 0)
@@ -361,3 +368,49 @@ int launch_gather(const moe_bf16* x, const int32_t* perm, const int32_t* offsets
 }
 
 }  // namespace moe
+
+// ---- the permutation without a context and without any allocation -------------------------
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_static_mutex;
+int32_t* g_static_tables[kMaxDevices] = {};   // per device: address of that GPU's copy of `scratch`
+
+// Address of the current device's copy of the static array (looked up once per device, with
+// that device current). Host code never uses the array's name as a pointer.
+int static_tables(int32_t** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return MOE_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    if (g_static_tables[dev] == nullptr) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) {
+            (void)hipGetLastError();
+            return MOE_ERR_HIP;
+        }
+        g_static_tables[dev] = static_cast<int32_t*>(p);
+    }
+    *out = g_static_tables[dev];
+    return MOE_OK;
+}
+
+}  // namespace
+
+extern "C" int moe_permute_static(const int32_t* topk_idx, int32_t T, int32_t k, int32_t E,
+                                  int32_t* counts, int32_t* offsets, int32_t* perm,
+                                  int32_t* inv_perm, void* stream) {
+    if (T < 0 || k < 1 || E < 1 || E > moe::kMaxExperts || k > E || k > moe::kWave)
+        return MOE_ERR_INVALID_ARG;
+    if (static_cast<long long>(T) * k >= (1LL << 31)) return MOE_ERR_INVALID_ARG;
+    if (!counts || !offsets) return MOE_ERR_INVALID_ARG;
+    if (T > 0 && (!topk_idx || !perm || !inv_perm)) return MOE_ERR_INVALID_ARG;
+    const int R = T * k;
+    if (moe::permute_scratch_ints(R, E) > 2 * kStaticTableInts) return MOE_ERR_UNSUPPORTED_SHAPE;
+    int32_t* tables = nullptr;
+    const int rc = static_tables(&tables);
+    if (rc != MOE_OK) return rc;
+    // Every table entry that a kernel reads is written earlier in the same call (the histogram
+    // kernel stores all E counts of every segment), so nothing has to be cleared.
+    return moe::launch_permute(topk_idx, R, E, counts, offsets, perm, inv_perm, tables,
+                               static_cast<hipStream_t>(stream));
+}
