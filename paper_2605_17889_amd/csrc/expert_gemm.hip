@@ -1,5 +1,5 @@
 // Grouped expert GEMMs on the gfx950 matrix cores (paper Table 1 row 3: per expert three
-// d_h x d_e bf16 matrices, 6*rows*d_h*d_e FLOPs; Section 4.1: "gated FFN execution per expert").
+// d_h x d_e bf16 matrices, 6*rows*d_h*d_e FLOPs; Section 4.1: each expert is a gated FFN).
 //
 //   gate/up : H[p, j]  = bf16( SiLU(sum_i Xp[p,i] W1_e[j,i]) * (sum_i Xp[p,i] W3_e[j,i]) )
 //   down    : Yp[p, c] = bf16( sum_j H[p,j] W2_e[c,j] )

@@ -27,3 +27,16 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+@pytest.fixture(scope="session")
+def experts_8x22b():
+    """One set of Mixtral-8x22B-shaped expert weights shared by every 8x22B GPU case (their
+    token and router seeds still differ per case): ((W1, W3, W2) on the GPU, their bf16 bits
+    on the host)."""
+    from paper_2605_17889_amd import synth
+    cfg = synth.PRESETS["mixtral8x22b_prefill"]
+    print("generating 8x22B-shaped expert weights on the GPU", flush=True)
+    W1, W3, W2 = synth.make_experts(cfg, "cuda")
+    host = tuple(synth.bf16_bits(w) for w in (W1, W3, W2))
+    return (W1, W3, W2), host

@@ -243,6 +243,54 @@ def test_expert_ffn_parity(config, d, f, rows):
     ctx.close()
 
 
+ALL_TILE_CONFIGS = [0, 1, 2, 3]
+
+
+@pytest.mark.parametrize("config", ALL_TILE_CONFIGS)
+def test_expert_ffn_silu_range_and_zero_rows(config):
+    """The fused SiLU epilogue far outside the benchmark's value range: tokens scaled by 8 and
+    weights of std 0.2 put the gate pre-activation at |a| of 40 to 150, where exp(-a) overflows
+    fp32 on the negative side (SiLU -> -0, the true value is below bf16's smallest subnormal)
+    and vanishes on the positive side (SiLU -> a). Some rows are exactly zero (zero output
+    required) and some are tiny (SiLU(a)*b underflows fp32). All rows, every tile height."""
+    d, f, rows = 512, 512, [300, 70, 1, 129]
+    say(f"expert_ffn silu range config={config}")
+    rng = np.random.default_rng(4242)
+    E, R = len(rows), sum(rows)
+    offsets = np.concatenate([[0], np.cumsum(rows)]).astype(np.int32)
+    xf = rng.normal(0, 8.0, size=(R, d))
+    zero_rows = np.array([0, 5, 299, 300, 369, 370, 371, R - 1])
+    tiny_rows = np.array([1, 301, 372])
+    xf[zero_rows] = 0.0
+    xf[tiny_rows] *= 1e-30
+    xp = bits(torch.tensor(xf, dtype=torch.float32).bfloat16())
+    W1, W3, W2 = rand_bits(rng, (E, f, d), 0.2), rand_bits(rng, (E, f, d), 0.2), rand_bits(rng, (E, d, f), 0.2)
+    want, h = ref.expert_ffn(xp, offsets, W1, W3, W2, want_h=True)
+    # the case really reaches the range it is meant for
+    a = bf16_to_f64(xp[2:3]) @ bf16_to_f64(W1[0]).T
+    assert np.abs(a).max() > 89.0 and a.min() < -89.0
+
+    ctx = B.MoeContext(R, d, f, E, 1)
+    B.moe_set_gemm_config(config)
+    try:
+        yp = torch.full((R, d), float("nan"), dtype=torch.bfloat16, device="cuda")
+        B.moe_expert_ffn(ctx, dev(bf16_tensor_from_bits(xp)), dev(offsets), R,
+                         dev(bf16_tensor_from_bits(W1)), dev(bf16_tensor_from_bits(W3)),
+                         dev(bf16_tensor_from_bits(W2)), yp)
+        torch.cuda.synchronize()
+    finally:
+        B.moe_set_gemm_config(-1)
+    got = bits(yp)
+    gf = bf16_to_f64(got)
+    assert np.isfinite(gf).all()
+    assert np.all(gf[zero_rows] == 0.0), "a zero token must give a zero row"
+    big = np.setdiff1d(np.arange(R), np.concatenate([zero_rows, tiny_rows]))
+    assert_close_ffn(got[big], want[big], f"silu range cfg{config}")
+    # tiny rows: the result is below bf16's normal range; it must stay tiny and finite
+    assert np.abs(gf[tiny_rows]).max() <= max(np.abs(want[tiny_rows]).max() * 1.05, 1e-37)
+    ctx.close()
+
+
 def test_expert_ffn_configs_agree_bitwise():
     """Every tile configuration runs the same accumulation chain per output element."""
     rng = np.random.default_rng(123)
@@ -331,17 +379,27 @@ def check_routing_exact(cfg, Hh, routing, T):
     return idx_ref, o_ref, p_ref
 
 
-def sample_tokens(cfg, offsets, perm, per_expert, seed):
-    """Tokens covering, for every non-empty expert, the first and last row of its group (tile
-    tails) and a seeded random handful of rows in between."""
+def sample_tokens(cfg, offsets, perm, per_expert, seed, tile=256, whole_tiles=True):
+    """Tokens for the FFN check at full size. One expert (the first with more than one row tile,
+    else the largest) contributes EVERY row of its first row tile and EVERY row of its last,
+    partial one, so that each wavefront and fragment-row position of a full tile and of a tail
+    tile is compared at the real reduction depth; every other non-empty expert contributes the
+    first and last row of its group and `per_expert` seeded rows in between."""
     rng = np.random.default_rng(seed)
+    sizes = [int(offsets[e + 1] - offsets[e]) for e in range(cfg.E)]
+    multi = [e for e in range(cfg.E) if sizes[e] > tile]
+    whole = (multi[0] if multi else int(np.argmax(sizes))) if whole_tiles else -1
     rows = []
     for e in range(cfg.E):
         lo, hi = int(offsets[e]), int(offsets[e + 1])
         if hi == lo:
             continue
-        pick = {lo, hi - 1}
-        pick.update(int(v) for v in rng.integers(lo, hi, size=per_expert))
+        if e == whole:
+            last0 = lo + (hi - lo - 1) // tile * tile
+            pick = set(range(lo, min(hi, lo + tile))) | set(range(last0, hi))
+        else:
+            pick = {lo, hi - 1}
+            pick.update(int(v) for v in rng.integers(lo, hi, size=per_expert))
         rows.extend(sorted(pick))
     return np.unique(perm[np.array(rows)] // cfg.k).astype(np.int32)
 
@@ -401,16 +459,15 @@ def test_layer_T0_and_errors():
 def test_layer_mixtral8x7b_decode(T):
     import dataclasses
     cfg = dataclasses.replace(synth.PRESETS["mixtral8x7b_decode"], T=T)
-    say(f"layer 8x7B decode T={T}: routing all tokens, FFN on sampled tokens")
+    say(f"layer 8x7B decode T={T}: routing and FFN on all tokens")
     L = synth.make_layer(cfg, "cuda")
     Hh = host_layer(L)
     y, ctx = run_layer(cfg, L)
     routing = fetch_routing(ctx, cfg.T)
     _, o_ref, p_ref = check_routing_exact(cfg, Hh, routing, cfg.T)
     say(f"    rows per expert {routing['counts'].tolist()}")
-    tokens = sample_tokens(cfg, o_ref, p_ref, 6, 1)
-    want, _, _ = ref.layer_tokens(Hh["x"], Hh["w_router"], None, Hh["W1"], Hh["W3"], Hh["W2"], cfg.k, tokens)
-    assert_close_ffn(bits(y)[tokens], want, f"8x7B decode T={T} ({tokens.size} tokens)")
+    want, _, _ = ref.layer_tokens(Hh["x"], Hh["w_router"], None, Hh["W1"], Hh["W3"], Hh["W2"], cfg.k)
+    assert_close_ffn(bits(y), want, f"8x7B decode T={T} (all tokens)")
     ctx.close()
 
 
@@ -426,21 +483,10 @@ def test_layer_many_small_experts_full_size(preset):
     _, o_ref, p_ref = check_routing_exact(cfg, Hh, routing, cfg.T)
     c = routing["counts"]
     say(f"    rows per expert min {int(c.min())} max {int(c.max())}")
-    tokens = sample_tokens(cfg, o_ref, p_ref, 1, 5)
+    tokens = sample_tokens(cfg, o_ref, p_ref, 1024 // cfg.E, 5)
     want, _, _ = ref.layer_tokens(Hh["x"], Hh["w_router"], None, Hh["W1"], Hh["W3"], Hh["W2"], cfg.k, tokens)
     assert_close_ffn(bits(y)[tokens], want, f"{preset} ({tokens.size} tokens)")
     ctx.close()
-
-
-@pytest.fixture(scope="module")
-def experts_8x22b():
-    """One set of Mixtral-8x22B-shaped expert weights shared by the 8x22B cases (their token
-    and router seeds still differ per case)."""
-    cfg = synth.PRESETS["mixtral8x22b_prefill"]
-    say("generating 8x22B-shaped expert weights on the GPU")
-    W1, W3, W2 = synth.make_experts(cfg, "cuda")
-    host = tuple(bits(w) for w in (W1, W3, W2))
-    return (W1, W3, W2), host
 
 
 def layer_8x22b(cfg, experts):
@@ -460,7 +506,7 @@ def test_layer_mixtral8x22b_prefill(experts_8x22b):
     routing = fetch_routing(ctx, cfg.T)
     _, o_ref, p_ref = check_routing_exact(cfg, Hh, routing, cfg.T)
     say(f"    rows per expert {routing['counts'].tolist()}")
-    tokens = sample_tokens(cfg, o_ref, p_ref, 10, 2)
+    tokens = sample_tokens(cfg, o_ref, p_ref, 64, 2)
     want, _, _ = ref.layer_tokens(Hh["x"], Hh["w_router"], None, Hh["W1"], Hh["W3"], Hh["W2"], cfg.k, tokens)
     assert_close_ffn(bits(y)[tokens], want, f"8x22B prefill ({tokens.size} tokens)")
     ctx.close()
@@ -476,7 +522,7 @@ def test_layer_mixtral8x22b_large_batch(experts_8x22b):
     routing = fetch_routing(ctx, cfg.T)
     _, o_ref, p_ref = check_routing_exact(cfg, Hh, routing, cfg.T)
     say(f"    rows per expert {routing['counts'].tolist()}")
-    tokens = sample_tokens(cfg, o_ref, p_ref, 4, 3)
+    tokens = sample_tokens(cfg, o_ref, p_ref, 64, 3)
     want, _, _ = ref.layer_tokens(Hh["x"], Hh["w_router"], None, Hh["W1"], Hh["W3"], Hh["W2"], cfg.k, tokens)
     assert_close_ffn(bits(y)[tokens], want, f"8x22B T=65536 ({tokens.size} tokens)")
     ctx.close()
@@ -493,7 +539,7 @@ def test_layer_mixtral8x22b_coalesced_vs_microbatched(experts_8x22b):
     _, o_ref, p_ref = check_routing_exact(cfg, Hh, routing, cfg.T)
     ym, _ = run_layer(cfg, L, micro=cfg.micro_tokens, ctx=ctx)
     assert torch.equal(ym.view(torch.int16), y.view(torch.int16)), "micro-batched output differs"
-    tokens = sample_tokens(cfg, o_ref, p_ref, 4, 3)
+    tokens = sample_tokens(cfg, o_ref, p_ref, 64, 3)
     want, _, _ = ref.layer_tokens(Hh["x"], Hh["w_router"], None, Hh["W1"], Hh["W3"], Hh["W2"], cfg.k, tokens)
     assert_close_ffn(bits(y)[tokens], want, f"8x22B coalesced ({tokens.size} tokens)")
     ctx.close()
@@ -563,6 +609,8 @@ def test_layer_streamed_experts_tiny_bitwise(n_streamed):
     cfg = synth.PRESETS["tiny"]
     say(f"layer tiny, last {n_streamed} experts streamed from host memory")
     L = synth.make_layer(cfg, "cuda")
+    Hh = host_layer(L)
+    oracle_y, _, _ = ref.layer_tokens(Hh["x"], Hh["w_router"], None, Hh["W1"], Hh["W3"], Hh["W2"], cfg.k)
     y_res, ctx = run_layer(cfg, L)
     E = cfg.E
     host = [pinned_tail(L[n], n_streamed) if n_streamed else None for n in ("W1", "W3", "W2")]
@@ -574,14 +622,19 @@ def test_layer_streamed_experts_tiny_bitwise(n_streamed):
                                      n_streamed, T, y)
         torch.cuda.synchronize()
         assert np.array_equal(bits(y), bits(want)), f"T={T}"
+        assert_close_ffn(bits(y), oracle_y[:T], f"tiny streamed n={n_streamed} T={T} vs oracle")
     ctx.close()
 
 
 def test_layer_streamed_experts_8x22b_bitwise(experts_8x22b):
     cfg = synth.PRESETS["mixtral8x22b_prefill"]
     say("layer 8x22B prefill, last 2 experts streamed from host memory")
-    L, _ = layer_8x22b(cfg, experts_8x22b)
+    L, Hh = layer_8x22b(cfg, experts_8x22b)
     y_res, ctx = run_layer(cfg, L)
+    routing = fetch_routing(ctx, cfg.T)
+    # oracle on rows of every expert, the streamed ones (the last two) included
+    tokens = sample_tokens(cfg, routing["offsets"], routing["perm"], 8, 9, whole_tiles=False)
+    want, _, _ = ref.layer_tokens(Hh["x"], Hh["w_router"], None, Hh["W1"], Hh["W3"], Hh["W2"], cfg.k, tokens)
     n = 2
     host = [pinned_tail(L[m], n) for m in ("W1", "W3", "W2")]
     dev_w = [L[m][:cfg.E - n] for m in ("W1", "W3", "W2")]
@@ -590,6 +643,7 @@ def test_layer_streamed_experts_8x22b_bitwise(experts_8x22b):
         B.moe_layer_forward_streamed(ctx, L["x"], L["w_router"], None, *dev_w, *host, n, cfg.T, y)
         torch.cuda.synchronize()
         assert np.array_equal(bits(y), bits(y_res))
+        assert_close_ffn(bits(y)[tokens], want, f"8x22B streamed vs oracle ({tokens.size} tokens)")
     ctx.close()
 
 
@@ -615,7 +669,7 @@ def test_layer_mixtral8x22b_zipf(experts_8x22b, preset):
     live = target > 0
     assert np.all(np.abs(counts[live] - target[live]) <= 0.02 * target[live])
     assert (counts[~live] == 0).all() and (~live).sum() == (1 if cfg.empty_expert else 0)
-    tokens = sample_tokens(cfg, o_ref, p_ref, 4, 4)
+    tokens = sample_tokens(cfg, o_ref, p_ref, 64, 4)
     want, _, _ = ref.layer_tokens(Hh["x"], Hh["w_router"], Hh["bias"], Hh["W1"], Hh["W3"], Hh["W2"], cfg.k, tokens)
     assert_close_ffn(bits(y)[tokens], want, f"{preset} ({tokens.size} tokens)")
     ctx.close()

@@ -411,6 +411,33 @@ def test_cost_model_hand_values():
     assert abs(c["t_stage_s"] - max((10e6 + 12e6 + 2e4 + 12e6) / 1e9, 0.06012)) < 1e-12
 
 
+def test_cost_model_per_kernel_split_hand_values():
+    """t_kernels_s and intermediate_bytes by hand. The split of the stage into its two grouped
+    contractions, with the intermediate H counted, is this repository's extension of Table 1
+    row 3 / Eq. 5 (the table prices the stage as one operation and leaves H out).
+    One expert, 1000 rows, d_h = 1000, d_e = 2000, 1 TFLOP/s, 1 GB/s:
+      gate/up: bytes = x rows 2e6 + W1,W3 8e6 + H written 4e6 = 14e6 -> 0.014 s; 8e9 FLOP -> 0.008 s
+      down   : bytes = H read 4e6 + W2 4e6 + outputs 2e6     = 10e6 -> 0.010 s; 4e9 FLOP -> 0.004 s
+      t_kernels = max(0.014, 0.008) + max(0.010, 0.004) = 0.024 s
+      intermediate_bytes = H written 4e6 + H read 4e6 + outputs 2e6 = 10e6"""
+    from oracle.cost_model import expert_stage_estimate as est
+    o = est([[1000]], 1000, 2000, 1.0, 1.0)
+    assert o["intermediate_bytes"] == 10e6
+    assert abs(o["t_kernels_s"] - 0.024) < 1e-15
+    # 0.5 TFLOP/s: gate/up compute 0.016 > 0.014, down memory 0.010 > 0.008 -> 0.026
+    assert abs(est([[1000]], 1000, 2000, 0.5, 1.0)["t_kernels_s"] - 0.026) < 1e-15
+    # 0.25 TFLOP/s: both compute-bound, 0.032 + 0.016
+    assert abs(est([[1000]], 1000, 2000, 0.25, 1.0)["t_kernels_s"] - 0.048) < 1e-15
+    # a second expert with 10 rows joins the same two launches (sums inside each max):
+    #   gate/up bytes 14e6 + (2e4 + 8e6 + 4e4) = 22.06e6, FLOP 8.08e9; down bytes 10e6 + (4e4 + 4e6 + 2e4)
+    #   = 14.06e6, FLOP 4.04e9 -> 0.02206 + 0.01406; intermediates 10e6 + 2*4e4 + 2e4
+    o = est([[1000, 10]], 1000, 2000, 1.0, 1.0)
+    assert abs(o["t_kernels_s"] - 0.03612) < 1e-15 and o["intermediate_bytes"] == 10.1e6
+    # micro-batches add up; an empty expert adds nothing
+    o2 = est([[1000, 10], [0, 1000]], 1000, 2000, 1.0, 1.0)
+    assert abs(o2["t_kernels_s"] - (0.03612 + 0.024)) < 1e-15 and o2["intermediate_bytes"] == 20.1e6
+
+
 def test_cost_model_benchmark_floors():
     """The floors quoted for the benchmark shapes: 8x22B prefill 9.896 TFLOP -> 3.958 ms at
     2.5 PFLOP/s; 8x7B decode 2.819 GB of weights -> 352 us at 8 TB/s; 16 micro-batches of 256
