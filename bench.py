@@ -9,12 +9,14 @@ GEMM, measured with HIP events on the launch stream inside the timed region), pe
 figures, and the CPU oracle timed on the host cores on a bounded token sample.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--micro M]
-                    [--tokens T] [--streamed N] [--planner-sweep] [--gemm-config C]
+                    [--tokens T] [--streamed N] [--planner-sweep] [--gemm-config C] [--rotate N]
 """
 import argparse
+import glob
 import json
 import os
 import sys
+import threading
 import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
@@ -24,11 +26,53 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA peak
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E peak
 
-# Bytes one launch of the gate/up kernel moves past L2 (rocprofv3 FETCH_SIZE + WRITE_SIZE, each
-# scaled by what the same counter reads for a plain 1 GiB copy: 2.00 and 1.00). Measured with the
-# commands recorded in profiles/expert_gemm_mixtral8x22b_prefill_hbm_traffic.md; it cannot be
-# measured from inside this process, so workloads without a recorded value report null.
-MEASURED_TRAFFIC_BYTES = {"mixtral8x22b_prefill": 11.79e9 + 0.592e9}
+NOMINAL_SCLK_MHZ = 2400.0       # the shader clock the published peaks are quoted at
+
+# Bytes ONE launch of the gate/up kernel moves past L2, from two rocprofv3 --pmc runs of this
+# file (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same counter reads for a plain
+# 1 GiB copy (--copy-calibration: 2.00 and 1.00). A process cannot read these counters for
+# itself, so the figure is a RECORDED one: it is reported only for the workload and call form it
+# was taken on, together with the profile file that holds the command and the per-kernel rows,
+# and it describes the library as it was when that file was written. Other runs report null.
+RECORDED_TRAFFIC = {
+    # (workload, micro_tokens): (bytes per gate/up launch, profile file)
+}
+
+
+class ClockSampler:
+    """Shader clock while the timed region runs, from the amdgpu hwmon file (no tool is spawned):
+    the median of the samples, so that the fraction of the peak AT THE CLOCK THE CHIP ACTUALLY RAN
+    can be reported beside the fraction of the nominal peak."""
+
+    def __init__(self):
+        files = glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/freq1_input")
+        self.path = files[0] if files else None
+        self.samples = []
+        self._stop = threading.Event()
+        self._thread = None
+
+    def _run(self):
+        while not self._stop.is_set():
+            try:
+                with open(self.path) as fh:
+                    self.samples.append(float(fh.read().strip()) / 1e6)
+            except (OSError, ValueError):
+                pass
+            time.sleep(0.004)
+
+    def start(self):
+        if self.path:
+            self._thread = threading.Thread(target=self._run, daemon=True)
+            self._thread.start()
+
+    def stop(self):
+        self._stop.set()
+        if self._thread:
+            self._thread.join()
+        if not self.samples:
+            return None
+        v = sorted(self.samples)
+        return v[len(v) // 2]
 
 
 def log(*a):
@@ -74,9 +118,15 @@ def cpu_baseline(cfg, L, target_seconds=15.0):
     n = int(max(probe, min(cfg.T, 2048, probe * target_seconds / max(dt, 1e-3))))
     if n > probe:
         dt = run(n)
-    return {"value": n / dt, "unit": "tokens/s", "cores": threads, "kind": "oracle",
-            "sample": f"{n} seeded tokens of the same {cfg.name} batch (tokens are independent in "
-                      f"the oracle), {dt:.2f} s wall, double precision, OpenMP over tokens"}
+    out = {"value": n / dt, "unit": "tokens/s", "cores": threads, "kind": "oracle",
+           "sample": f"{n} seeded tokens of the same {cfg.name} batch (tokens are independent in "
+                     f"the oracle), {dt:.2f} s wall, double precision, OpenMP over tokens"}
+    if cfg.name == "tiny":                 # small enough to time on one core as well
+        ref.set_threads(1)
+        dt1 = run(n)
+        ref.set_threads(threads)
+        out["single_thread_value"] = n / dt1
+    return out
 
 
 SUSTAINED_TFLOPS = 1330.0      # this library's gate/up kernel on large uniform expert groups
@@ -146,6 +196,10 @@ def main():
     ap.add_argument("--graph", action="store_true",
                     help="capture one step into a HIP graph after the warm-up and time replays "
                          "(per-stage event timing is off in this mode)")
+    ap.add_argument("--rotate", type=int, default=0,
+                    help="keep N copies of the tokens and expert weights and give every step the "
+                         "next one, so that no operand of a step is still in a cache from the step "
+                         "before (for presets whose weights fit the 256 MB Infinity Cache)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--gemm-config", type=int, default=-1,
                     help="force the expert-GEMM tile configuration (0 large, 1 medium, 2 small, "
@@ -184,10 +238,10 @@ def main():
         import dataclasses
         cfg = dataclasses.replace(cfg, T=args.tokens)
     T = cfg.T
-    B.moe_set_gemm_config(args.gemm_config)
     log(f"[bench] generating {cfg.name}: T={T} d={cfg.d_model} f={cfg.d_ff} E={cfg.E} k={cfg.k}")
     L = synth.make_layer(cfg, "cuda")
     ctx = B.MoeContext(T, cfg.d_model, cfg.d_ff, cfg.E, cfg.k)
+    B.moe_set_gemm_config(ctx, args.gemm_config)
     if cfg.zipf_s is not None:
         idx = torch.empty((T, cfg.k), dtype=torch.int32, device="cuda")
         w = torch.empty((T, cfg.k), dtype=torch.float32, device="cuda")
@@ -238,19 +292,33 @@ def main():
                     "sum_ms": moved / h2d * 1e3 + resident_ms,
                     "estimate_ms": max(moved / h2d * 1e3, resident_ms)}
 
+    copies = [L]
+    if args.rotate > 1:
+        if streamed is not None or args.graph:
+            log("bench.py: --rotate does not combine with --streamed or --graph")
+            sys.exit(2)
+        copies += [{n: (v.clone() if n in ("x", "W1", "W3", "W2") else v) for n, v in L.items()}
+                   for _ in range(args.rotate - 1)]
+    turn = [0]
+
     def step():
         if streamed is not None:
             B.moe_layer_forward_streamed(ctx, L["x"], L["w_router"], L["bias"], *dev_w, *host_w,
                                          args.streamed, T, y)
-        elif args.micro > 0:
-            B.moe_layer_forward_microbatched(ctx, L["x"], L["w_router"], L["bias"], L["W1"], L["W3"],
-                                             L["W2"], T, args.micro, y)
+            return
+        Lc = copies[turn[0] % len(copies)]
+        turn[0] += 1
+        if args.micro > 0:
+            B.moe_layer_forward_microbatched(ctx, Lc["x"], Lc["w_router"], Lc["bias"], Lc["W1"],
+                                             Lc["W3"], Lc["W2"], T, args.micro, y)
         else:
-            B.moe_layer_forward(ctx, L["x"], L["w_router"], L["bias"], L["W1"], L["W3"], L["W2"], T, y)
+            B.moe_layer_forward(ctx, Lc["x"], Lc["w_router"], Lc["bias"], Lc["W1"], Lc["W3"],
+                                Lc["W2"], T, y)
 
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    sclk_mhz = None
     if args.graph:
         if streamed is not None:
             log("bench.py: --graph and --streamed do not combine (the transfers use a second stream)")
@@ -275,11 +343,14 @@ def main():
         stage_ms, launches, calls = B.moe_profile_end(ctx)
     else:
         B.moe_profile_begin(ctx, args.steps)
+        clock = ClockSampler()
+        clock.start()
         t0 = time.perf_counter()
         for _ in range(args.steps):
             step()
         torch.cuda.synchronize()
         elapsed = time.perf_counter() - t0
+        sclk_mhz = clock.stop()
         stage_ms, launches, calls = B.moe_profile_end(ctx)
     counts = torch.empty(cfg.E, dtype=torch.int32, device="cuda")
     B.moe_last_routing(ctx, min(T, args.micro) if args.micro > 0 else T, counts=counts)
@@ -305,12 +376,18 @@ def main():
     dom_launch_ms = dom["ms_per_step"] / max(dom["launches_per_step"], 1)
     dom_flops_per_launch = model["gateup"]["flops"] / max(dom["launches_per_step"], 1)
     achieved = dom_flops_per_launch / (dom_launch_ms * 1e-3) / 1e12
-    roofline = {"kernel": "grouped_gemm_ring_kernel<gate/up, fused SiLU*mul>", "bound": "mfma",
+    recorded = RECORDED_TRAFFIC.get((cfg.name if args.tokens <= 0 else None, args.micro or None))
+    roofline = {"kernel": "gate/up grouped GEMM (fused SiLU*mul epilogue)", "bound": "mfma",
                 "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": achieved / PEAK_BF16_TFLOPS,
-                "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name) if args.micro == 0 else None,
+                "traffic": recorded[0] if recorded else None,
+                "traffic_source": recorded[1] if recorded else None,
                 "avg_launch_ms": dom_launch_ms,
                 "algorithmic_flops_per_launch": dom_flops_per_launch}
+    if sclk_mhz:
+        # the published peak is quoted at 2.4 GHz; under load the chip runs slower
+        roofline["sclk_MHz_median_during_timed_steps"] = sclk_mhz
+        roofline["frac_of_measured_clock_peak"] = achieved / (PEAK_BF16_TFLOPS * sclk_mhz / NOMINAL_SCLK_MHZ)
 
     out = {
         "metric": "MoE-layer tokens/sec and expert-GEMM TFLOP/s (% bf16 MFMA peak), 8x22B shape",
@@ -319,6 +396,7 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": cfg.name, "T": T, "d_model": cfg.d_model, "d_ff": cfg.d_ff, "E": cfg.E,
                    "k": cfg.k, "micro_tokens": args.micro or None, "hip_graph": bool(args.graph),
+                   "rotated_buffers": args.rotate if args.rotate > 1 else None,
                    "rows_per_expert_last_call": counts.cpu().tolist()},
         "expert_gemm_TFLOP/s": gemm_tflops,
         "expert_gemm_frac_of_bf16_peak": gemm_tflops / PEAK_BF16_TFLOPS,

@@ -17,8 +17,11 @@
  *     one after the work that the call enqueued has finished.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream). Calls enqueue
  *     work and return without synchronising the host; results are ready when the stream is.
- *   - Return value: MOE_OK or a negative moe_status. Arguments are checked on the host
- *     before anything is enqueued; on an argument error nothing has been launched.
+ *   - Return value: MOE_OK or a negative moe_status. Arguments are checked on the host, and
+ *     whatever a call must allocate is allocated, before anything is enqueued: when a call returns
+ *     MOE_ERR_INVALID_ARG, MOE_ERR_UNSUPPORTED_SHAPE or MOE_ERR_WORKSPACE nothing has been
+ *     launched. MOE_ERR_HIP reports a failed launch or runtime call in the middle of the
+ *     sequence: the stages before it are already enqueued and the outputs are undefined.
  *   - T = 0 is legal and a no-op. An expert that receives no row is legal.
  *   - The calls that take `stream` only enqueue kernels (and, for moe_last_routing, device
  *     copies) on it: after one ordinary call of the same kind and shape (the first launch of a
@@ -76,9 +79,10 @@ enum {
     MOE_NUM_STAGES = 6
 };
 
-/* Create a context for `shape` on GPU `device_id`; allocates the workspace (routing tables,
- * x_perm, H and y_perm for T_max tokens). Returns MOE_ERR_UNSUPPORTED_SHAPE for shapes
- * outside the supported set, MOE_ERR_WORKSPACE if the device allocation fails. */
+/* Create a context for `shape` on GPU `device_id` (0..63); allocates the workspace (routing
+ * tables, x_perm, H and y_perm for T_max tokens) there and leaves the calling thread's current
+ * device as it was. Returns MOE_ERR_UNSUPPORTED_SHAPE for shapes outside the supported set,
+ * MOE_ERR_WORKSPACE if the device allocation fails. */
 int moe_create(moe_ctx** out, const moe_shape* shape, int device_id);
 
 /* Release the context and its workspace. The caller must have drained the stream. */
@@ -255,7 +259,8 @@ int moe_estimate_streamed_stage(const moe_shape* shape, const int32_t* rows, int
                                 const moe_machine* machine, double pcie_gbytes_per_s,
                                 int32_t inputs_on_device, moe_streamed_estimate* out);
 
-/* Tuning / testing knob, process-wide: force the expert-GEMM tile configuration
+/* Tuning / testing knob of ONE context (it lasts until changed; set it from the thread that uses
+ * the context): force the expert-GEMM tile configuration
  * (0 = large, 1 = medium, 2 = small, 3 = tiny rows-per-expert tile) or -1 for the automatic choice by
  * average rows per expert. Adding 16 to any of these makes the medium and small tiles load the
  * weights as ordinary (cached) lines, adding 32 as non-temporal ones; without either the library
@@ -265,7 +270,7 @@ int moe_estimate_streamed_stage(const moe_shape* shape, const int32_t* rows, int
  * itself when T*d_model*2 bytes do not fit 32 bits) instead of reading token rows through the
  * permutation. Every setting produces identical bits (same accumulation chain per
  * output element); only speed differs. Returns MOE_ERR_INVALID_ARG for other values. */
-int moe_set_gemm_config(int config);
+int moe_set_gemm_config(moe_ctx* ctx, int config);
 
 #ifdef __cplusplus
 }

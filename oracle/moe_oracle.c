@@ -197,7 +197,7 @@ int moe_ref_gather(const uint16_t* x, const int32_t* perm, int R, int d, int k, 
 
 /* ---------------------------------------------------------------------------------------
  * One expert applied to one row (Table 1 row 3: three d_h x d_e matrices; Section 4.1:
- * "gated FFN"):  a = W1 x, b = W3 x, h = SiLU(a) * b, o = W2 h.
+ * a gated FFN):  a = W1 x, b = W3 x, h = SiLU(a) * b, o = W2 h.
  * W1, W3 are [f, d] row-major (out, in); W2 is [d, f] row-major. All sums in double.
  * ------------------------------------------------------------------------------------- */
 static void expert_row(const double* xd, const uint16_t* W1e, const uint16_t* W3e,

@@ -276,5 +276,5 @@ def moe_estimate_streamed_stage(d_model: int, d_ff: int, rows, n_moved: int, tfl
     return {n: getattr(out, n) for n, _ in MoeStreamedEstimate._fields_}
 
 
-def moe_set_gemm_config(config: int):
-    _check(lib().moe_set_gemm_config(C.c_int(config)), "moe_set_gemm_config")
+def moe_set_gemm_config(ctx: MoeContext, config: int):
+    _check(lib().moe_set_gemm_config(ctx._h, C.c_int(config)), "moe_set_gemm_config")

@@ -40,11 +40,19 @@ int launch_permute(const int32_t* topk_idx, int R, int E, int32_t* counts, int32
                    int32_t* perm, int32_t* inv_perm, int32_t* scratch, hipStream_t s);
 int launch_gather(const moe_bf16* x, const int32_t* perm, const int32_t* offsets, int R, int d,
                   int k, int E, moe_bf16* x_perm, hipStream_t s);
-int launch_gateup(const moe_bf16* a, const int32_t* row_index, int index_div,
+// Where and how a context launches its expert GEMMs: its device and the tuning knobs of
+// moe_set_gemm_config (all settings give identical bits).
+struct GemmEnv {
+    int device = 0;
+    int forced_config = -1;           // -1: automatic; 0..3: force a tile configuration
+    int stream_mode = -1;             // -1: automatic; 0: weights never non-temporal; 1: always
+    bool materialise_gather = false;  // layer calls write x_perm instead of fusing the gather
+};
+int launch_gateup(const GemmEnv& env, const moe_bf16* a, const int32_t* row_index, int index_div,
                   const int32_t* offsets, int R, int R_hint, int d, int f, int E,
                   const moe_bf16* W1, const moe_bf16* W3, moe_bf16* H, hipStream_t s);
-int launch_down(const moe_bf16* H, const int32_t* offsets, int R, int R_hint, int d, int f, int E,
-                const moe_bf16* W2, moe_bf16* y_perm, hipStream_t s);
+int launch_down(const GemmEnv& env, const moe_bf16* H, const int32_t* offsets, int R, int R_hint,
+                int d, int f, int E, const moe_bf16* W2, moe_bf16* y_perm, hipStream_t s);
 int launch_combine(const moe_bf16* y_perm, const int32_t* inv_perm, const float* topk_w, int T,
                    int d, int k, moe_bf16* y, hipStream_t s);
 

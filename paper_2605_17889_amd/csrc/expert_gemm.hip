@@ -10,6 +10,7 @@
 // tile). Every output element is one accumulator chain over k = 0,16,32,... with the same
 // MFMA instruction in every tile configuration, so results do not depend on how many rows an
 // expert has or which configuration is picked (coalesced == micro-batched, bit for bit).
+#include <atomic>
 #include <cmath>
 
 #include "expert_gemm_kernel.h"
@@ -22,7 +23,7 @@ using gemm::Config;
 // NA, NB > 0 launch the pipelined kernel with operand rings of NA and NB stages; otherwise the
 // generic kernel with Cfg::NSTAGE stages.
 template <class Cfg, int NA = 0, int NB = 0>
-int launch_grouped(const moe_bf16* A, const moe_bf16* B0, const moe_bf16* B1, moe_bf16* C,
+int launch_grouped(const GemmEnv& env, const moe_bf16* A, const moe_bf16* B0, const moe_bf16* B1, moe_bf16* C,
                    const int32_t* offsets, const int32_t* row_index, int index_div, int R, int E,
                    int N, int K, hipStream_t s) {
     constexpr bool RING = NA > 0;
@@ -40,12 +41,16 @@ int launch_grouped(const moe_bf16* A, const moe_bf16* B0, const moe_bf16* B1, mo
         smem = Cfg::SMEM;
     }
     constexpr int kThreads = Cfg::NTHREADS;
-    static bool attr_set = false;
-    if (!attr_set) {
+    // The attribute belongs to the kernel's code object on ONE device: one bit per device, set
+    // by whichever thread launches this kernel there first (setting it twice is harmless).
+    static std::atomic<uint64_t> attr_set{0};
+    if (env.device < 0 || env.device >= 64) return MOE_ERR_INVALID_ARG;
+    const uint64_t bit = 1ull << env.device;
+    if (!(attr_set.load(std::memory_order_acquire) & bit)) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
             return MOE_ERR_HIP;
-        attr_set = true;
+        attr_set.fetch_or(bit, std::memory_order_release);
     }
     const long long max_mt = R / Cfg::BM + E;                  // >= sum_e ceil(M_e / BM)
     long long grid = max_mt * (N / Cfg::BN_OUT);
@@ -57,11 +62,8 @@ int launch_grouped(const moe_bf16* A, const moe_bf16* B0, const moe_bf16* B1, mo
 }
 
 // Tile configuration by average rows per expert. All configurations give identical bits.
-int g_forced_config = -1;   // -1: automatic; 0,1,2: force (tests / tuning)
-int g_stream_mode = -1;     // -1: automatic; 0: weights never non-temporal; 1: always (medium/small)
-
-int pick_config(int R, int E) {
-    if (g_forced_config >= 0) return g_forced_config;
+int pick_config(const GemmEnv& env, int R, int E) {
+    if (env.forced_config >= 0) return env.forced_config;
     // 0: pipelined 256x256 tiles. 1: 128-row tiles (generic kernel). 2: a few dozen rows per
     // expert (64-row tiles). 3: a handful (32-row tiles, deep weight ring). Between 0 and 1 the padded rows decide: groups a little above a multiple
     // of 256 rows waste most of a large tile. Per-expert counts are not known on the host, so
@@ -79,8 +81,8 @@ int pick_config(int R, int E) {
 
 // Weights may be loaded as non-temporal when (almost) every expert has a single m-tile: then no
 // other tile asks for the same weight bytes and keeping them cached only displaces the rows.
-bool single_m_tile(int R, int E, int BM) {
-    if (g_stream_mode >= 0) return g_stream_mode != 0;
+bool single_m_tile(const GemmEnv& env, int R, int E, int BM) {
+    if (env.stream_mode >= 0) return env.stream_mode != 0;
     const double avg = static_cast<double>(R) / (E > 0 ? E : 1);
     return avg + 2.0 * std::sqrt(avg) <= BM;
 }
@@ -107,73 +109,68 @@ using DownTinyNarrowS = Config<32, 64, 64, 1, 2, 11, false, true>;   // more, na
 
 }  // namespace
 
-void set_gemm_config(int cfg, int stream_mode) {
-    g_forced_config = cfg;
-    g_stream_mode = stream_mode;
-}
-
 // `a` is the grouped activation matrix [R, d] when row_index is NULL; otherwise it is the
 // token matrix [T, d] and grouped row p reads token row_index[p] / index_div (the caller makes
 // sure that T * d * 2 bytes fit a 32-bit offset). R bounds the rows of the E launched experts
 // (it sizes the grid); R_hint is how many rows they are expected to hold together (it picks the
 // tile configuration): the two differ when a call covers a subset of a layer's experts.
-int launch_gateup(const moe_bf16* a, const int32_t* row_index, int index_div,
+int launch_gateup(const GemmEnv& env, const moe_bf16* a, const int32_t* row_index, int index_div,
                   const int32_t* offsets, int R, int R_hint, int d, int f, int E,
                   const moe_bf16* W1, const moe_bf16* W3, moe_bf16* H, hipStream_t s) {
     if (R == 0) return MOE_OK;
     const moe_bf16* x_perm = a;
-    int config = pick_config(R_hint, E);
+    int config = pick_config(env, R_hint, E);
     if (config == 0 && d / 64 < 3) config = 1;     // the pipelined kernel needs three k-steps
     switch (config) {
-        case 0: return launch_grouped<GateUpLarge, 2, 3>(x_perm, W1, W3, H, offsets, row_index, index_div, R, E, f, d, s);
+        case 0: return launch_grouped<GateUpLarge, 2, 3>(env, x_perm, W1, W3, H, offsets, row_index, index_div, R, E, f, d, s);
         case 1:
-            if (single_m_tile(R_hint, E, 128))
-                return launch_grouped<GateUpMidS>(x_perm, W1, W3, H, offsets, row_index, index_div, R, E, f, d, s);
-            return launch_grouped<GateUpMid>(x_perm, W1, W3, H, offsets, row_index, index_div, R, E, f, d, s);
+            if (single_m_tile(env, R_hint, E, 128))
+                return launch_grouped<GateUpMidS>(env, x_perm, W1, W3, H, offsets, row_index, index_div, R, E, f, d, s);
+            return launch_grouped<GateUpMid>(env, x_perm, W1, W3, H, offsets, row_index, index_div, R, E, f, d, s);
         case 3:
-            if (single_m_tile(R_hint, E, 32))
-                return launch_grouped<GateUpTinyS>(x_perm, W1, W3, H, offsets, row_index, index_div, R, E, f, d, s);
-            return launch_grouped<GateUpTiny>(x_perm, W1, W3, H, offsets, row_index, index_div, R, E, f, d, s);
+            if (single_m_tile(env, R_hint, E, 32))
+                return launch_grouped<GateUpTinyS>(env, x_perm, W1, W3, H, offsets, row_index, index_div, R, E, f, d, s);
+            return launch_grouped<GateUpTiny>(env, x_perm, W1, W3, H, offsets, row_index, index_div, R, E, f, d, s);
         default:
-            if (single_m_tile(R_hint, E, 64))
-                return launch_grouped<GateUpSmallS>(x_perm, W1, W3, H, offsets, row_index, index_div, R, E, f, d, s);
-            return launch_grouped<GateUpSmall>(x_perm, W1, W3, H, offsets, row_index, index_div, R, E, f, d, s);
+            if (single_m_tile(env, R_hint, E, 64))
+                return launch_grouped<GateUpSmallS>(env, x_perm, W1, W3, H, offsets, row_index, index_div, R, E, f, d, s);
+            return launch_grouped<GateUpSmall>(env, x_perm, W1, W3, H, offsets, row_index, index_div, R, E, f, d, s);
     }
 }
 
-int launch_down(const moe_bf16* H, const int32_t* offsets, int R, int R_hint, int d, int f, int E,
-                const moe_bf16* W2, moe_bf16* y_perm, hipStream_t s) {
+int launch_down(const GemmEnv& env, const moe_bf16* H, const int32_t* offsets, int R, int R_hint,
+                int d, int f, int E, const moe_bf16* W2, moe_bf16* y_perm, hipStream_t s) {
     if (R == 0) return MOE_OK;
-    int config = pick_config(R_hint, E);
+    int config = pick_config(env, R_hint, E);
     if (config == 0 && f / 64 < 3) config = 1;     // the pipelined kernel needs three k-steps
     switch (config) {
-        case 0: return launch_grouped<DownLarge, 2, 3>(H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
+        case 0: return launch_grouped<DownLarge, 2, 3>(env, H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
         case 1:
             // HBM-bound: wide tiles stream more bytes per workgroup, but only if there are
             // enough of them to occupy the 256 compute units (about one m-tile per expert).
             if (static_cast<long long>(E) * (d / 256) >= 160 && d % 256 == 0) {
-                if (single_m_tile(R_hint, E, 128))
-                    return launch_grouped<DownMidWideS>(H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
-                return launch_grouped<DownMidWide>(H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
+                if (single_m_tile(env, R_hint, E, 128))
+                    return launch_grouped<DownMidWideS>(env, H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
+                return launch_grouped<DownMidWide>(env, H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
             }
-            if (single_m_tile(R_hint, E, 128))
-                return launch_grouped<DownMidS>(H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
-            return launch_grouped<DownMid>(H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
+            if (single_m_tile(env, R_hint, E, 128))
+                return launch_grouped<DownMidS>(env, H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
+            return launch_grouped<DownMid>(env, H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
         case 3:
             // with fewer routed rows than experts only about R experts have a tile: narrower
             // tiles so that their weights still stream through most compute units
-            if (static_cast<long long>(R_hint < E ? R_hint : E) * (d / 128) < 192 && single_m_tile(R_hint, E, 32))
-                return launch_grouped<DownTinyNarrowS>(H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
+            if (static_cast<long long>(R_hint < E ? R_hint : E) * (d / 128) < 192 && single_m_tile(env, R_hint, E, 32))
+                return launch_grouped<DownTinyNarrowS>(env, H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
             if (d % 128 == 0) {
-                if (single_m_tile(R_hint, E, 32))
-                    return launch_grouped<DownTinyS>(H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
-                return launch_grouped<DownTiny>(H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
+                if (single_m_tile(env, R_hint, E, 32))
+                    return launch_grouped<DownTinyS>(env, H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
+                return launch_grouped<DownTiny>(env, H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
             }
             [[fallthrough]];
         default:
-            if (single_m_tile(R_hint, E, 64))
-                return launch_grouped<DownSmallS>(H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
-            return launch_grouped<DownSmall>(H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
+            if (single_m_tile(env, R_hint, E, 64))
+                return launch_grouped<DownSmallS>(env, H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
+            return launch_grouped<DownSmall>(env, H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
     }
 }
 

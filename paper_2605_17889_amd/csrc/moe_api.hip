@@ -5,13 +5,10 @@
 
 #include "common.h"
 
-namespace moe {
-void set_gemm_config(int cfg, int stream_mode);
-}
-
 struct moe_ctx {
     moe_shape shape;
     int device;
+    moe::GemmEnv gemm;   // device + tuning knobs of moe_set_gemm_config
     // workspace (device)
     unsigned char* base;
     size_t bytes;
@@ -43,8 +40,6 @@ struct moe_ctx {
 namespace {
 
 using namespace moe;
-
-bool g_materialise_gather = false;   // testing knob: take the unfused path at any size
 
 bool shape_ok(const moe_shape* s) {
     if (!s) return false;
@@ -126,7 +121,7 @@ int forward_chunk(moe_ctx* c, const moe_bf16* x, const float* w_router, const fl
     // The row gather x -> x_perm is fused into the gate/up kernel's operand loads (it reads
     // token row perm[p] / k directly) whenever a token row's byte offset fits 32 bits.
     const bool fuse_gather =
-        !g_materialise_gather && static_cast<unsigned long long>(T) * d * 2ull < (1ull << 32);
+        !c->gemm.materialise_gather && static_cast<unsigned long long>(T) * d * 2ull < (1ull << 32);
     if (!fuse_gather) {
         rc = run_stage(c, MOE_STAGE_GATHER, 1, s, [&] {
             return launch_gather(x, c->perm, c->offsets, R, d, k, E, c->x_perm, s);
@@ -135,12 +130,12 @@ int forward_chunk(moe_ctx* c, const moe_bf16* x, const float* w_router, const fl
     }
     rc = run_stage(c, MOE_STAGE_GATEUP, 1, s, [&] {
         return fuse_gather
-                   ? launch_gateup(x, c->perm, k, c->offsets, R, R, d, f, E, W1, W3, c->H, s)
-                   : launch_gateup(c->x_perm, nullptr, 1, c->offsets, R, R, d, f, E, W1, W3, c->H, s);
+                   ? launch_gateup(c->gemm, x, c->perm, k, c->offsets, R, R, d, f, E, W1, W3, c->H, s)
+                   : launch_gateup(c->gemm, c->x_perm, nullptr, 1, c->offsets, R, R, d, f, E, W1, W3, c->H, s);
     });
     if (rc != MOE_OK) return rc;
     rc = run_stage(c, MOE_STAGE_DOWN, 1, s, [&] {
-        return launch_down(c->H, c->offsets, R, R, d, f, E, W2, c->y_perm, s);
+        return launch_down(c->gemm, c->H, c->offsets, R, R, d, f, E, W2, c->y_perm, s);
     });
     if (rc != MOE_OK) return rc;
     return run_stage(c, MOE_STAGE_COMBINE, 1, s, [&] {
@@ -209,18 +204,26 @@ int moe_create(moe_ctx** out, const moe_shape* shape, int device_id) {
     int ndev = 0;
     if (hipGetDeviceCount(&ndev) != hipSuccess) return MOE_ERR_HIP;
     if (device_id < 0 || device_id >= ndev) return MOE_ERR_INVALID_ARG;
-    MOE_HIP_TRY(hipSetDevice(device_id));
+    if (device_id >= 64) return MOE_ERR_INVALID_ARG;
+    int caller_device = 0;
+    MOE_HIP_TRY(hipGetDevice(&caller_device));
     moe_ctx* c = new (std::nothrow) moe_ctx();
     if (!c) return MOE_ERR_WORKSPACE;
     c->shape = *shape;
     c->device = device_id;
+    c->gemm.device = device_id;
     const Layout L = layout_for(shape);
     c->bytes = L.total;
     void* p = nullptr;
-    if (hipMalloc(&p, L.total) != hipSuccess) {
+    // allocate on the context's device, then give the caller its current device back
+    hipError_t err = hipSetDevice(device_id);
+    if (err == hipSuccess) err = hipMalloc(&p, L.total);
+    const hipError_t back = hipSetDevice(caller_device);
+    if (err != hipSuccess || back != hipSuccess) {
         (void)hipGetLastError();
+        if (p) (void)hipFree(p);
         delete c;
-        return MOE_ERR_WORKSPACE;
+        return err != hipSuccess && back == hipSuccess ? MOE_ERR_WORKSPACE : MOE_ERR_HIP;
     }
     c->base = static_cast<unsigned char*>(p);
     c->topk_idx = reinterpret_cast<int32_t*>(c->base + L.topk_idx);
@@ -308,9 +311,9 @@ int moe_expert_ffn(moe_ctx* c, const moe_bf16* x_perm, const int32_t* offsets, i
     if (!x_perm || !offsets || !W1 || !W3 || !W2 || !y_perm) return MOE_ERR_INVALID_ARG;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const moe_shape& sh = c->shape;
-    int rc = launch_gateup(x_perm, nullptr, 1, offsets, R, R, sh.d_model, sh.d_ff, sh.E, W1, W3, c->H, s);
+    int rc = launch_gateup(c->gemm, x_perm, nullptr, 1, offsets, R, R, sh.d_model, sh.d_ff, sh.E, W1, W3, c->H, s);
     if (rc != MOE_OK) return rc;
-    return launch_down(c->H, offsets, R, R, sh.d_model, sh.d_ff, sh.E, W2, y_perm, s);
+    return launch_down(c->gemm, c->H, offsets, R, R, sh.d_model, sh.d_ff, sh.E, W2, y_perm, s);
 }
 
 int moe_combine(moe_ctx* c, const moe_bf16* y_perm, const int32_t* inv_perm, const float* topk_w,
@@ -405,11 +408,11 @@ int moe_layer_forward_streamed(moe_ctx* c, const moe_bf16* x, const float* w_rou
     auto ffn = [&](int e0, int n, const moe_bf16* w1, const moe_bf16* w3, const moe_bf16* w2) -> int {
         const int hint = static_cast<int>(static_cast<long long>(R) * n / E);
         int r = run_stage(c, MOE_STAGE_GATEUP, 1, s, [&] {
-            return launch_gateup(x, c->perm, k, c->offsets + e0, R, hint, d, f, n, w1, w3, c->H, s);
+            return launch_gateup(c->gemm, x, c->perm, k, c->offsets + e0, R, hint, d, f, n, w1, w3, c->H, s);
         });
         if (r != MOE_OK) return r;
         return run_stage(c, MOE_STAGE_DOWN, 1, s, [&] {
-            return launch_down(c->H, c->offsets + e0, R, hint, d, f, n, w2, c->y_perm, s);
+            return launch_down(c->gemm, c->H, c->offsets + e0, R, hint, d, f, n, w2, c->y_perm, s);
         });
     };
     if (E_res > 0 && (rc = ffn(0, E_res, W1, W3, W2)) != MOE_OK) return rc;
@@ -480,20 +483,22 @@ int moe_profile_end(moe_ctx* c, double* stage_ms, int64_t* stage_launches, int32
     return rc;
 }
 
-/* Tuning/testing knob: force the expert-GEMM tile configuration (0 large, 1 medium, 2 small,
- * 3 tiny rows-per-expert), or -1 for the automatic choice; +16 never loads weights as non-temporal,
- * +32 always does (medium and small tiles); +64 makes the layer calls write the gathered rows
- * to the workspace instead of reading them through the permutation. All settings give
- * identical bits. */
-int moe_set_gemm_config(int config) {
+/* Tuning/testing knob of one context: force the expert-GEMM tile configuration (0 large, 1 medium,
+ * 2 small, 3 tiny rows-per-expert), or -1 for the automatic choice; +16 never loads weights as
+ * non-temporal, +32 always does (medium and small tiles); +64 makes the layer calls write the
+ * gathered rows to the workspace instead of reading them through the permutation. All settings
+ * give identical bits. */
+int moe_set_gemm_config(moe_ctx* c, int config) {
+    if (!c) return MOE_ERR_INVALID_ARG;
     int stream_mode = -1;
     bool materialise = false;
     if (config >= 63) { materialise = true; config -= 64; }
     if (config >= 31) { stream_mode = 1; config -= 32; }
     else if (config >= 15) { stream_mode = 0; config -= 16; }
     if (config < -1 || config > 3) return MOE_ERR_INVALID_ARG;
-    g_materialise_gather = materialise;
-    moe::set_gemm_config(config, stream_mode);
+    c->gemm.materialise_gather = materialise;
+    c->gemm.forced_config = config;
+    c->gemm.stream_mode = stream_mode;
     return MOE_OK;
 }
 

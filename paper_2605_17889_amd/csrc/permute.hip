@@ -61,6 +61,7 @@ __global__ __launch_bounds__(kBlockWaves* kWave) void hist_many_kernel(
         if (my < 0 || my >= E) my = -1;
         const uint64_t same = same_value_lanes(my);
         if (my >= 0 && (same & lanemask_lt(lane)) == 0) cnt[my] += __popcll(same);
+        __builtin_amdgcn_wave_barrier();    // rounds stay in order for the compiler too
     }
     for (int e = lane; e < E; e += kWave) seg_hist[static_cast<size_t>(seg) * E + e] = cnt[e];
 }
@@ -224,8 +225,11 @@ __global__ __launch_bounds__(kBlockWaves* kWave) void scatter_many_kernel(
             pos = start + __popcll(same & lanemask_lt(lane));
         }
         // ... then its first lane writes (a wavefront executes the two steps in lockstep, and
-        // LDS operations of one wavefront complete in order)
+        // LDS operations of one wavefront complete in order; the fence keeps the compiler from
+        // moving the read below the write)
+        __builtin_amdgcn_wave_barrier();
         if (my >= 0 && (same & lanemask_lt(lane)) == 0) run[my] = pos + __popcll(same);
+        __builtin_amdgcn_wave_barrier();
         if (i < R) {
             inv_perm[i] = pos;
             if (pos >= 0) perm[pos] = static_cast<int32_t>(i);
@@ -257,6 +261,7 @@ __global__ __launch_bounds__(kSmallWaves* kWave) void permute_small_kernel(
         if (my[r] < 0 || my[r] >= E) my[r] = -1;
         same[r] = same_value_lanes(my[r]);
         if (my[r] >= 0 && (same[r] & lanemask_lt(lane)) == 0) mine[my[r]] += __popcll(same[r]);
+        __builtin_amdgcn_wave_barrier();
     }
     __syncthreads();
     if (tid < E) {                            // segments of one expert, in order
@@ -303,7 +308,9 @@ __global__ __launch_bounds__(kSmallWaves* kWave) void permute_small_kernel(
         const int64_t i = base + r * kWave + lane;
         int pos = -1;
         if (my[r] >= 0) pos = mine[my[r]] + __popcll(same[r] & lanemask_lt(lane));
+        __builtin_amdgcn_wave_barrier();      // every lane of a set has read before its first lane writes
         if (my[r] >= 0 && (same[r] & lanemask_lt(lane)) == 0) mine[my[r]] = pos + __popcll(same[r]);
+        __builtin_amdgcn_wave_barrier();
         if (i < R) {
             inv_perm[i] = pos;
             if (pos >= 0) perm[pos] = static_cast<int32_t>(i);

@@ -81,11 +81,9 @@ def test_null_arguments_are_rejected_before_any_gpu_work(lib):
     assert lib.moe_layer_forward(None, None, None, None, None, None, None, 4, None, None) == -1
     assert lib.moe_layer_forward_streamed(None, None, None, None, None, None, None, None, None, None,
                                           1, 4, None, None) == -1
-    assert lib.moe_set_gemm_config(9) == -1
-    assert lib.moe_set_gemm_config(4 + 32) == -1
-    assert lib.moe_set_gemm_config(4 + 64) == -1
-    for ok in (0, 3, 1 + 16, -1 + 32, -1 + 64, 2 + 32 + 64, -1):
-        assert lib.moe_set_gemm_config(ok) == 0
+    assert lib.moe_set_gemm_config(None, 0) == -1
+    assert lib.moe_permute_static(None, -1, 2, 8, None, None, None, None, None) == -1
+    assert lib.moe_permute_static(None, 4, 3, 2, None, None, None, None, None) == -1
 
 
 def test_binding_fails_loudly_without_gpu():

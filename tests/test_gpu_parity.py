@@ -228,7 +228,7 @@ def test_expert_ffn_parity(config, d, f, rows):
     want = ref.expert_ffn(xp, offsets, W1, W3, W2)
 
     ctx = B.MoeContext(R, d, f, E, 1)
-    B.moe_set_gemm_config(config)
+    B.moe_set_gemm_config(ctx, config)
     try:
         yp = torch.full((R, d), float("nan"), dtype=torch.bfloat16, device="cuda")
         B.moe_expert_ffn(ctx, dev(bf16_tensor_from_bits(xp)), dev(offsets), R,
@@ -236,7 +236,7 @@ def test_expert_ffn_parity(config, d, f, rows):
                          dev(bf16_tensor_from_bits(W2)), yp)
         torch.cuda.synchronize()
     finally:
-        B.moe_set_gemm_config(-1)
+        B.moe_set_gemm_config(ctx, -1)
     got = bits(yp)
     assert not np.isnan(bf16_to_f64(got)).any()
     assert_close_ffn(got, want, f"expert_ffn cfg{config}")
@@ -271,7 +271,7 @@ def test_expert_ffn_silu_range_and_zero_rows(config):
     assert np.abs(a).max() > 89.0 and a.min() < -89.0
 
     ctx = B.MoeContext(R, d, f, E, 1)
-    B.moe_set_gemm_config(config)
+    B.moe_set_gemm_config(ctx, config)
     try:
         yp = torch.full((R, d), float("nan"), dtype=torch.bfloat16, device="cuda")
         B.moe_expert_ffn(ctx, dev(bf16_tensor_from_bits(xp)), dev(offsets), R,
@@ -279,7 +279,7 @@ def test_expert_ffn_silu_range_and_zero_rows(config):
                          dev(bf16_tensor_from_bits(W2)), yp)
         torch.cuda.synchronize()
     finally:
-        B.moe_set_gemm_config(-1)
+        B.moe_set_gemm_config(ctx, -1)
     got = bits(yp)
     gf = bf16_to_f64(got)
     assert np.isfinite(gf).all()
@@ -303,13 +303,13 @@ def test_expert_ffn_configs_agree_bitwise():
     outs = []
     try:
         for config in (0, 1, 2, 3, 1 + 32, 3 + 16):
-            B.moe_set_gemm_config(config)
+            B.moe_set_gemm_config(ctx, config)
             yp = torch.empty((R, d), dtype=torch.bfloat16, device="cuda")
             B.moe_expert_ffn(ctx, xp, dev(offsets), R, W1, W3, W2, yp)
             torch.cuda.synchronize()
             outs.append(bits(yp))
     finally:
-        B.moe_set_gemm_config(-1)
+        B.moe_set_gemm_config(ctx, -1)
     assert all(np.array_equal(outs[0], o) for o in outs[1:])
     ctx.close()
 
@@ -437,6 +437,17 @@ def test_layer_tiny_ragged_T(T):
     ctx.close()
 
 
+def test_gemm_config_values():
+    """The tuning knob belongs to one context and validates its argument."""
+    ctx = B.MoeContext(16, 512, 256, 8, 2)
+    for bad in (9, 4 + 32, 4 + 64, -2):
+        with pytest.raises(B.MoeError):
+            B.moe_set_gemm_config(ctx, bad)
+    for ok in (0, 3, 1 + 16, -1 + 32, -1 + 64, 2 + 32 + 64, -1):
+        B.moe_set_gemm_config(ctx, ok)
+    ctx.close()
+
+
 def test_layer_T0_and_errors():
     cfg = synth.PRESETS["tiny"]
     L = synth.make_layer(cfg, "cuda")
@@ -553,12 +564,12 @@ def test_layer_with_materialised_gather_bitwise(preset):
     say(f"layer {preset}: gather materialised vs fused into the gate/up loads")
     L = synth.make_layer(cfg, "cuda")
     y_fused, ctx = run_layer(cfg, L)
-    B.moe_set_gemm_config(-1 + 64)
+    B.moe_set_gemm_config(ctx, -1 + 64)
     try:
         y_plain, _ = run_layer(cfg, L, ctx=ctx)
         y_micro, _ = run_layer(cfg, L, micro=100, ctx=ctx)
     finally:
-        B.moe_set_gemm_config(-1)
+        B.moe_set_gemm_config(ctx, -1)
     assert np.array_equal(bits(y_plain), bits(y_fused))
     assert np.array_equal(bits(y_micro), bits(y_fused))
     ctx.close()
@@ -623,6 +634,42 @@ def test_layer_streamed_experts_tiny_bitwise(n_streamed):
         torch.cuda.synchronize()
         assert np.array_equal(bits(y), bits(want)), f"T={T}"
         assert_close_ffn(bits(y), oracle_y[:T], f"tiny streamed n={n_streamed} T={T} vs oracle")
+    ctx.close()
+
+
+@pytest.mark.parametrize("n_streamed", [1, 3])
+def test_layer_streamed_back_to_back_without_host_sync(n_streamed):
+    """Three streamed calls enqueued one behind the other with no host synchronisation in
+    between, each with its own pinned weight set. The stream is kept busy beforehand so that all
+    three calls are enqueued while the first has not started: the copy stream could then run
+    ahead of the kernels, and only the wait for a slot's `freed` event (recorded by the previous
+    call's last use of that slot) keeps a later call's weights from overwriting the ones an
+    earlier call has yet to use. Each output must equal the resident call with that call's weights."""
+    import dataclasses
+    cfg = synth.PRESETS["tiny"]
+    say(f"layer tiny, three streamed calls back to back, last {n_streamed} experts from host memory")
+    E, T = cfg.E, cfg.T
+    ctx = B.MoeContext(T, cfg.d_model, cfg.d_ff, E, cfg.k)
+    base = synth.make_layer(cfg, "cuda")
+    sets, want = [], []
+    for seed in (0, 21, 22):
+        W = synth.make_experts(dataclasses.replace(cfg, seed=seed), "cuda")
+        L = dict(base, W1=W[0], W3=W[1], W2=W[2])
+        sets.append(L)
+        want.append(bits(run_layer(cfg, L, ctx=ctx)[0]).copy())
+    assert not np.array_equal(want[0], want[1])
+    host = [[pinned_tail(L[n], n_streamed) for n in ("W1", "W3", "W2")] for L in sets]
+    devw = [[L[n][:E - n_streamed].contiguous() for n in ("W1", "W3", "W2")] for L in sets]
+    ys = [torch.full((T, cfg.d_model), float("nan"), dtype=torch.bfloat16, device="cuda") for _ in sets]
+    busy = torch.randn((8192, 8192), device="cuda", dtype=torch.bfloat16)
+    torch.cuda.synchronize()
+    for _ in range(40):                       # tens of milliseconds of queued work
+        busy = (busy @ busy).clamp_(-1, 1)
+    for L, h, dw, y in zip(sets, host, devw, ys):
+        B.moe_layer_forward_streamed(ctx, L["x"], L["w_router"], None, *dw, *h, n_streamed, T, y)
+    torch.cuda.synchronize()
+    for i, y in enumerate(ys):
+        assert np.array_equal(bits(y), want[i]), f"call {i} used another call's weights"
     ctx.close()
 
 
