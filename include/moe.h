@@ -268,7 +268,8 @@ int moe_estimate_streamed_stage(const moe_shape* shape, const int32_t* rows, int
  * weight byte is used once. Adding 64 makes moe_layer_forward and its micro-batched form write
  * the gathered rows x_perm to the workspace and run the gate/up GEMM on them (the path taken by
  * itself when T*d_model*2 bytes do not fit 32 bits) instead of reading token rows through the
- * permutation. Every setting produces identical bits (same accumulation chain per
+ * permutation. Adding 128 keeps the 256-row tiles of a last round that is less than half full
+ * whole (by default each is run as two 128-row halves). Every setting produces identical bits (same accumulation chain per
  * output element); only speed differs. Returns MOE_ERR_INVALID_ARG for other values. */
 int moe_set_gemm_config(moe_ctx* ctx, int config);
 

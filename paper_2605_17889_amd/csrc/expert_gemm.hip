@@ -20,30 +20,25 @@ namespace {
 
 using gemm::Config;
 
-// NA, NB > 0 launch the pipelined kernel with operand rings of NA and NB stages; otherwise the
-// generic kernel with Cfg::NSTAGE stages.
-template <class Cfg, int NA = 0, int NB = 0>
-int launch_grouped(const GemmEnv& env, const moe_bf16* A, const moe_bf16* B0, const moe_bf16* B1, moe_bf16* C,
-                   const int32_t* offsets, const int32_t* row_index, int index_div, int R, int E,
-                   int N, int K, hipStream_t s) {
-    constexpr bool RING = NA > 0;
-    if (N % Cfg::BN_OUT != 0 || K % Cfg::BK != 0) return MOE_ERR_UNSUPPORTED_SHAPE;
-    if (RING && K / Cfg::BK < (NA > NB ? NA : NB)) return MOE_ERR_UNSUPPORTED_SHAPE;
-    using Kernel = void (*)(const uint16_t*, const uint16_t*, const uint16_t*, uint16_t*,
-                            const int32_t*, const int32_t*, int, int, int, int);
-    Kernel kern;
-    int smem;
-    if constexpr (RING) {
-        kern = gemm::grouped_gemm_ring_kernel<Cfg, NA, NB>;
-        smem = gemm::RingCfg<Cfg, NA, NB>::SMEM;
-    } else {
-        kern = gemm::grouped_gemm_kernel<Cfg>;
-        smem = Cfg::SMEM;
+// Compute units of a device (rounds of the pipelined kernel are that many tiles long).
+int compute_units(int device) {
+    static std::atomic<int> cached[64];
+    int n = cached[device].load(std::memory_order_relaxed);
+    if (n == 0) {
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || n <= 0) {
+            (void)hipGetLastError();
+            n = 256;
+        }
+        cached[device].store(n, std::memory_order_relaxed);
     }
-    constexpr int kThreads = Cfg::NTHREADS;
+    return n;
+}
+
+template <class Kernel, class... Args>
+int launch_tiles(const GemmEnv& env, std::atomic<uint64_t>& attr_set, Kernel kern, int smem,
+                 int threads, long long grid, hipStream_t s, Args... args) {
     // The attribute belongs to the kernel's code object on ONE device: one bit per device, set
     // by whichever thread launches this kernel there first (setting it twice is harmless).
-    static std::atomic<uint64_t> attr_set{0};
     if (env.device < 0 || env.device >= 64) return MOE_ERR_INVALID_ARG;
     const uint64_t bit = 1ull << env.device;
     if (!(attr_set.load(std::memory_order_acquire) & bit)) {
@@ -52,13 +47,41 @@ int launch_grouped(const GemmEnv& env, const moe_bf16* A, const moe_bf16* B0, co
             return MOE_ERR_HIP;
         attr_set.fetch_or(bit, std::memory_order_release);
     }
-    const long long max_mt = R / Cfg::BM + E;                  // >= sum_e ceil(M_e / BM)
-    long long grid = max_mt * (N / Cfg::BN_OUT);
     grid = (grid + gemm::kXcds - 1) / gemm::kXcds * gemm::kXcds;
     if (grid > 0x7fffffffLL) return MOE_ERR_UNSUPPORTED_SHAPE;
-    hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(grid)), dim3(kThreads), smem, s,
-                       A, B0, B1, C, offsets, row_index, index_div, E, N, K);
+    hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(grid)), dim3(threads), smem, s, args...);
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
+}
+
+// The generic kernel with Cfg::NSTAGE stages.
+template <class Cfg>
+int launch_grouped(const GemmEnv& env, const moe_bf16* A, const moe_bf16* B0, const moe_bf16* B1, moe_bf16* C,
+                   const int32_t* offsets, const int32_t* row_index, int index_div, int R, int E,
+                   int N, int K, hipStream_t s) {
+    if (N % Cfg::BN_OUT != 0 || K % Cfg::BK != 0) return MOE_ERR_UNSUPPORTED_SHAPE;
+    static std::atomic<uint64_t> attr_set{0};
+    const long long max_mt = R / Cfg::BM + E;                  // >= sum_e ceil(M_e / BM)
+    return launch_tiles(env, attr_set, gemm::grouped_gemm_kernel<Cfg>, Cfg::SMEM, Cfg::NTHREADS,
+                        max_mt * (N / Cfg::BN_OUT), s, A, B0, B1, C, offsets, row_index, index_div,
+                        E, N, K);
+}
+
+// The pipelined kernel with operand rings of NA and NB stages; tiles of at most HalfCfg::BM rows
+// and the tiles of a last round that is less than half full run at half height.
+template <class Cfg, class HalfCfg, int NA, int NB>
+int launch_ring(const GemmEnv& env, const moe_bf16* A, const moe_bf16* B0, const moe_bf16* B1, moe_bf16* C,
+                const int32_t* offsets, const int32_t* row_index, int index_div, int R, int E,
+                int N, int K, hipStream_t s) {
+    if (N % Cfg::BN_OUT != 0 || K % Cfg::BK != 0) return MOE_ERR_UNSUPPORTED_SHAPE;
+    if (K / Cfg::BK < (NA > NB ? NA : NB)) return MOE_ERR_UNSUPPORTED_SHAPE;
+    static std::atomic<uint64_t> attr_set{0};
+    const int cus = env.split_last_round ? compute_units(env.device) : 0;
+    const long long max_mt = R / Cfg::BM + E;                  // >= sum_e ceil(M_e / BM)
+    // split tiles take two slots each: at most ceil(cus / 2 / 8) more slots in every XCD's range
+    const long long grid = max_mt * (N / Cfg::BN_OUT) + gemm::kXcds * ((cus / 2 + gemm::kXcds - 1) / gemm::kXcds + 1);
+    return launch_tiles(env, attr_set, gemm::grouped_gemm_ring_kernel<Cfg, HalfCfg, NA, NB>,
+                        gemm::RingCfg<Cfg, NA, NB>::SMEM, Cfg::NTHREADS, grid, s, A, B0, B1, C,
+                        offsets, row_index, index_div, E, N, K, cus);
 }
 
 // Tile configuration by average rows per expert. All configurations give identical bits.
@@ -89,7 +112,7 @@ bool single_m_tile(const GemmEnv& env, int R, int E, int BM) {
 
 //                      BM   BN  BK WM WN NSTAGE DUAL [STREAM_B]
 using GateUpLarge = Config<256, 256, 64, 2, 4, 2, true>;
-using GateUpMid   = Config<128, 256, 64, 2, 4, 3, true>;
+using GateUpMid   = Config<128, 256, 64, 2, 4, 3, true>;   // also the half-height tile of GateUpLarge
 using GateUpSmall = Config<64, 128, 64, 1, 2, 4, true>;
 using DownLarge   = Config<256, 256, 64, 2, 4, 2, false>;
 using DownMid     = Config<128, 128, 64, 2, 2, 4, false>;
@@ -122,7 +145,7 @@ int launch_gateup(const GemmEnv& env, const moe_bf16* a, const int32_t* row_inde
     int config = pick_config(env, R_hint, E);
     if (config == 0 && d / 64 < 3) config = 1;     // the pipelined kernel needs three k-steps
     switch (config) {
-        case 0: return launch_grouped<GateUpLarge, 2, 3>(env, x_perm, W1, W3, H, offsets, row_index, index_div, R, E, f, d, s);
+        case 0: return launch_ring<GateUpLarge, GateUpMid, 2, 3>(env, x_perm, W1, W3, H, offsets, row_index, index_div, R, E, f, d, s);
         case 1:
             if (single_m_tile(env, R_hint, E, 128))
                 return launch_grouped<GateUpMidS>(env, x_perm, W1, W3, H, offsets, row_index, index_div, R, E, f, d, s);
@@ -144,7 +167,7 @@ int launch_down(const GemmEnv& env, const moe_bf16* H, const int32_t* offsets, i
     int config = pick_config(env, R_hint, E);
     if (config == 0 && f / 64 < 3) config = 1;     // the pipelined kernel needs three k-steps
     switch (config) {
-        case 0: return launch_grouped<DownLarge, 2, 3>(env, H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
+        case 0: return launch_ring<DownLarge, DownMidWide, 2, 3>(env, H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
         case 1:
             // HBM-bound: wide tiles stream more bytes per workgroup, but only if there are
             // enough of them to occupy the 256 compute units (about one m-tile per expert).

@@ -35,7 +35,7 @@ typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kXcds = 8;     // workgroups are dealt round-robin to the 8 XCDs (own L2 each)
-constexpr int kGroupM = 8;   // m-tiles that sweep the n-tiles together (share weight tiles)
+constexpr int kGroupM = 8;   // at most this many m-tiles that sweep the n-tiles together (share weight tiles)
 
 struct TileCoord {
     int expert;      // -1: no tile for this workgroup
@@ -56,9 +56,15 @@ struct TileCoord {
 // the lane whose range holds the tile number broadcasts its expert. The cost does not grow
 // with the number of experts (a scalar loop over 128 experts would cost more than a tile of a
 // small expert).
+//
+// split_cus > 0 (the pipelined kernel passes the number of compute units): a launch of `total`
+// tiles runs in rounds of split_cus tiles, one per compute unit; when the last round is less
+// than half full, each of its tiles is handed to two workgroups as an upper and a lower half
+// of BM/2 rows, so that the round ends after a half-height tile instead of a full one. The
+// halves are the highest slots of every XCD's range, hence the last workgroups dispatched.
 template <int BM>
 __device__ __forceinline__ TileCoord locate_tile(const int32_t* __restrict__ offsets, int E,
-                                                 int NT) {
+                                                 int NT, int split_cus = 0) {
     constexpr int EW = kMaxExperts / kWave;
     TileCoord tc{-1, 0, 0, 0, 0, 1};
     const int lane = threadIdx.x & (kWave - 1);
@@ -87,8 +93,20 @@ __device__ __forceinline__ TileCoord locate_tile(const int32_t* __restrict__ off
     const int per = (total + kXcds - 1) / kXcds;
     const int xcd = blockIdx.x % kXcds;
     const int slot = blockIdx.x / kXcds;
-    const int L = xcd * per + slot;
-    if (slot >= per || L >= total) return tc;
+    const int len = max(0, min(per, total - xcd * per));   // tiles in this XCD's range
+    int halved = 0;                                        // of those, the last `halved` are split
+    if (split_cus > 0) {
+        const int rem = total % split_cus;
+        if (rem > 0 && 2 * rem <= split_cus) halved = min(len, (rem + kXcds - 1) / kXcds);
+    }
+    int tile_slot = slot, half = -1;
+    if (slot >= len - halved) {
+        const int j = slot - (len - halved);
+        if (j >= 2 * halved) return tc;
+        tile_slot = len - halved + (j >> 1);
+        half = j & 1;
+    }
+    const int L = xcd * per + tile_slot;
 #pragma unroll
     for (int w = 0; w < EW; ++w) {
         if (w * kWave >= E) continue;
@@ -98,19 +116,40 @@ __device__ __forceinline__ TileCoord locate_tile(const int32_t* __restrict__ off
         const int start = __builtin_amdgcn_readfirstlane(__shfl(incl[w] - tiles[w], src, kWave));
         const int m_e = __builtin_amdgcn_readfirstlane(__shfl(rows[w], src, kWave));
         const int row_e = __builtin_amdgcn_readfirstlane(__shfl(first[w], src, kWave));
+        // The expert's mt m-tiles form ceil(mt / kGroupM) groups of nearly equal height (the
+        // first `extra` groups hold one tile more), so that a short tail tile sweeps the n-tiles
+        // together with full tiles of its expert and finds the weight tiles in L2.
         const int mt = (m_e + BM - 1) / BM;
+        const int ngroups = (mt + kGroupM - 1) / kGroupM;
+        const int base = mt / ngroups, extra = mt - base * ngroups;
         const int local = L - start;
-        const int g = local / (kGroupM * NT);
-        const int head = g * kGroupM;
-        const int gm = min(kGroupM, mt - head);
-        const int in = local - g * (kGroupM * NT);
+        const int big = extra * (base + 1) * NT;       // tiles in the taller groups
+        int gm, head, in;
+        if (local < big) {
+            gm = base + 1;
+            const int g = local / (gm * NT);
+            head = g * gm;
+            in = local - g * (gm * NT);
+        } else {
+            gm = base;
+            const int g = (local - big) / (gm * NT);
+            head = extra * (base + 1) + g * gm;
+            in = local - big - g * (gm * NT);
+        }
         const int mi = head + in % gm;
+        int row0 = row_e + mi * BM, nrows = min(BM, m_e - mi * BM);
+        if (half >= 0) {
+            const int h0 = half * (BM / 2);
+            if (nrows <= h0) return tc;                // the tile has no lower half
+            row0 += h0;
+            nrows = min(BM / 2, nrows - h0);
+        }
         tc.expert = w * kWave + src;
         tc.mi = in % gm;
         tc.gm = gm;
         tc.nt = in / gm;
-        tc.row0 = row_e + mi * BM;
-        tc.rows = min(BM, m_e - mi * BM);
+        tc.row0 = row0;
+        tc.rows = nrows;
         return tc;
     }
     return tc;
@@ -466,7 +505,7 @@ __device__ __forceinline__ void ring_kstep(f32x4 (&acc)[Cfg::TM][Cfg::TN], bf16x
     using R = RingCfg<Cfg, NA, NB>;
     constexpr int TM = Cfg::TM, TN = Cfg::TN, LA = R::LA, LB = R::LB, LPW = LA + LB;
     constexpr int BPC = (TN + TM / 2 - 1) / (TM / 2);      // B reads per chunk (first chunks)
-    static_assert(TN <= TM && (LPW % TM == 0 || TM % LPW == 0), "interleave plan");
+    static_assert(TN <= TM, "interleave plan");
     static_assert(!PARTIAL || R::A_FIRST, "skipping A loads needs the B loads to be the newest");
     // ---- first half: MFMAs on (fa, fb0); read the second-half fragments of this k-step
     if (COMPUTE) {
@@ -512,31 +551,25 @@ __device__ __forceinline__ void ring_kstep(f32x4 (&acc)[Cfg::TM][Cfg::TN], bf16x
                     fb0[b] = lds16(pb_n0 + b * Cfg::TILE_STEP);
             }
         }
-        if (LPW >= TM) {
+        // the LPW loads of the k-step are spread evenly over the TM chunks
 #pragma unroll
-            for (int n = 0; n < LPW / TM; ++n) issue(i * (LPW / TM) + n);
-        } else if (i % (TM / LPW) == 0) {
-            issue(i / (TM / LPW));
-        }
+        for (int n = (i * LPW + TM - 1) / TM; n < ((i + 1) * LPW + TM - 1) / TM; ++n) issue(n);
         MOE_FENCE();
     }
 }
 
+// One tile of the pipelined kernel (all wavefronts of the workgroup call it together).
 template <class Cfg, int NA, int NB>
-__global__ __launch_bounds__(Cfg::NTHREADS) void grouped_gemm_ring_kernel(
-    const uint16_t* __restrict__ A, const uint16_t* __restrict__ B0,
-    const uint16_t* __restrict__ B1, uint16_t* __restrict__ C,
-    const int32_t* __restrict__ offsets, const int32_t* __restrict__ row_index, int index_div,
-    int E, int N, int K) {
+__device__ __forceinline__ void ring_tile(const TileCoord& tc, unsigned char* smem,
+                                          const uint16_t* __restrict__ A,
+                                          const uint16_t* __restrict__ B0,
+                                          const uint16_t* __restrict__ B1, uint16_t* __restrict__ C,
+                                          const int32_t* __restrict__ row_index, int index_div,
+                                          int N, int K) {
     using R = RingCfg<Cfg, NA, NB>;
     constexpr int BM = Cfg::BM, BK = Cfg::BK, WN = Cfg::WN, TM = Cfg::TM, TN = Cfg::TN;
     constexpr int LA = R::LA, LB = R::LB, AB = Cfg::A_BYTES, BB = Cfg::B_BYTES;
     static_assert(BK == 64, "64-k stages");
-
-    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
-
-    const TileCoord tc = locate_tile<BM>(offsets, E, N / Cfg::BN_OUT);
-    if (tc.expert < 0) return;                       // uniform for the whole workgroup
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -616,6 +649,30 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void grouped_gemm_ring_kernel(
     }
     mfma_drain();
     store_tile<Cfg>(acc, tc, fp, wm, wn, C, N);
+}
+
+// Tiles are enumerated at Cfg::BM rows. A tile that holds at most HalfCfg::BM = Cfg::BM / 2 rows
+// (an expert's short tail, or a half of a tile of the last, partial round: see locate_tile) runs
+// the same pipeline at half height: it issues half the MFMAs and A loads, and takes about 0.6 of
+// the time of a full tile. Every output element is still one accumulator chain over k, so the
+// bits do not depend on which height computed it.
+template <class Cfg, class HalfCfg, int NA, int NB>
+__global__ __launch_bounds__(Cfg::NTHREADS) void grouped_gemm_ring_kernel(
+    const uint16_t* __restrict__ A, const uint16_t* __restrict__ B0,
+    const uint16_t* __restrict__ B1, uint16_t* __restrict__ C,
+    const int32_t* __restrict__ offsets, const int32_t* __restrict__ row_index, int index_div,
+    int E, int N, int K, int split_cus) {
+    static_assert(HalfCfg::BM * 2 == Cfg::BM && HalfCfg::BN == Cfg::BN && HalfCfg::BK == Cfg::BK &&
+                  HalfCfg::NTHREADS == Cfg::NTHREADS && HalfCfg::DUAL == Cfg::DUAL, "same n-tiling");
+    static_assert(RingCfg<HalfCfg, NA, NB>::SMEM <= RingCfg<Cfg, NA, NB>::SMEM, "LDS of the full tile");
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+
+    const TileCoord tc = locate_tile<Cfg::BM>(offsets, E, N / Cfg::BN_OUT, split_cus);
+    if (tc.expert < 0) return;                       // uniform for the whole workgroup
+    if (tc.rows <= HalfCfg::BM)
+        ring_tile<HalfCfg, NA, NB>(tc, smem, A, B0, B1, C, row_index, index_div, N, K);
+    else
+        ring_tile<Cfg, NA, NB>(tc, smem, A, B0, B1, C, row_index, index_div, N, K);
 }
 
 }  // namespace gemm
