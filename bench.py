@@ -40,39 +40,47 @@ RECORDED_TRAFFIC = {
 
 
 class ClockSampler:
-    """Shader clock while the timed region runs, from the amdgpu hwmon file (no tool is spawned):
-    the median of the samples, so that the fraction of the peak AT THE CLOCK THE CHIP ACTUALLY RAN
-    can be reported beside the fraction of the nominal peak."""
+    """Shader clock and board power while the timed region runs, read from the amdgpu sysfs files
+    (no tool is spawned): medians of the samples, so that the fraction of the peak AT THE CLOCK
+    THE CHIP ACTUALLY RAN can be reported beside the fraction of the nominal peak."""
 
     def __init__(self):
-        files = glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/freq1_input")
-        self.path = files[0] if files else None
-        self.samples = []
+        def first(pattern):
+            files = sorted(glob.glob(pattern))
+            return files[0] if files else None
+        self.sclk = first("/sys/class/drm/card*/device/pp_dpm_sclk")
+        self.power = first("/sys/class/drm/card*/device/hwmon/hwmon*/power1_input")
+        self.mhz, self.watts = [], []
         self._stop = threading.Event()
         self._thread = None
 
     def _run(self):
         while not self._stop.is_set():
             try:
-                with open(self.path) as fh:
-                    self.samples.append(float(fh.read().strip()) / 1e6)
-            except (OSError, ValueError):
+                if self.sclk:
+                    with open(self.sclk) as fh:      # the active level is the line marked '*'
+                        for line in fh:
+                            if "*" in line:
+                                self.mhz.append(float(line.split(":")[1].lower().split("mhz")[0]))
+                if self.power:
+                    with open(self.power) as fh:
+                        self.watts.append(float(fh.read().strip()) / 1e6)
+            except (OSError, ValueError, IndexError):
                 pass
             time.sleep(0.004)
 
     def start(self):
-        if self.path:
+        if self.sclk or self.power:
             self._thread = threading.Thread(target=self._run, daemon=True)
             self._thread.start()
 
     def stop(self):
+        """-> (median MHz or None, median W or None)"""
         self._stop.set()
         if self._thread:
             self._thread.join()
-        if not self.samples:
-            return None
-        v = sorted(self.samples)
-        return v[len(v) // 2]
+        med = lambda v: sorted(v)[len(v) // 2] if v else None
+        return med(self.mhz), med(self.watts)
 
 
 def log(*a):
@@ -318,7 +326,7 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    sclk_mhz = None
+    sclk_mhz = board_w = None
     if args.graph:
         if streamed is not None:
             log("bench.py: --graph and --streamed do not combine (the transfers use a second stream)")
@@ -350,7 +358,7 @@ def main():
             step()
         torch.cuda.synchronize()
         elapsed = time.perf_counter() - t0
-        sclk_mhz = clock.stop()
+        sclk_mhz, board_w = clock.stop()
         stage_ms, launches, calls = B.moe_profile_end(ctx)
     counts = torch.empty(cfg.E, dtype=torch.int32, device="cuda")
     B.moe_last_routing(ctx, min(T, args.micro) if args.micro > 0 else T, counts=counts)
@@ -388,6 +396,8 @@ def main():
         # the published peak is quoted at 2.4 GHz; under load the chip runs slower
         roofline["sclk_MHz_median_during_timed_steps"] = sclk_mhz
         roofline["frac_of_measured_clock_peak"] = achieved / (PEAK_BF16_TFLOPS * sclk_mhz / NOMINAL_SCLK_MHZ)
+    if board_w:
+        roofline["board_power_W_median_during_timed_steps"] = board_w
 
     out = {
         "metric": "MoE-layer tokens/sec and expert-GEMM TFLOP/s (% bf16 MFMA peak), 8x22B shape",
