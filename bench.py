@@ -216,6 +216,12 @@ def main():
                     help="run the workload coalesced and as micro-batches of 64..T/2 tokens and "
                          "print, per micro-batch size, the measured expert-GEMM time next to the "
                          "roofline estimate of moe_estimate_expert_stage (markdown table)")
+    ap.add_argument("--vendor-gemm-yardstick", action="store_true",
+                    help="only time the vendor library's dense bf16 GEMM (torch.matmul) at the "
+                         "gate/up and down shapes of the workload with uniform expert groups "
+                         "folded into one matrix, with the same clock and power sampling: what a "
+                         "tuned dense kernel reaches on this machine at this shape (a yardstick "
+                         "for the expert GEMMs, not part of the path)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy 10 times (to scale rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE counters against a kernel of known traffic)")
@@ -240,6 +246,36 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"copy_calibration": {"bytes_read": 1 << 30, "bytes_written": 1 << 30,
                                                "launches": 10}}), flush=True)
+        return
+    if args.vendor_gemm_yardstick:
+        cfg = synth.PRESETS[args.workload]
+        R, d, f = (args.tokens or cfg.T) * cfg.k, cfg.d_model, cfg.d_ff
+        g = torch.Generator(device="cuda").manual_seed(1)
+        mk = lambda r, c, std: (torch.randn((r, c), generator=g, device="cuda") * std).to(torch.bfloat16)
+        out = {}
+        for name, (a, w) in {"gateup": (mk(R, d, 1.0), mk(2 * f, d, 0.02)),
+                             "down": (mk(R, f, 1.0), mk(d, f, 0.02))}.items():
+            flops = 2.0 * a.shape[0] * w.shape[0] * a.shape[1]
+            for _ in range(5):
+                torch.matmul(a, w.t())
+            torch.cuda.synchronize()
+            n = max(20, int(0.6 / (flops / 1.4e15)))          # about 0.6 s of work
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            clock = ClockSampler()
+            clock.start()
+            e0.record()
+            for _ in range(n):
+                torch.matmul(a, w.t())
+            e1.record()
+            torch.cuda.synchronize()
+            mhz, watts = clock.stop()
+            ms = e0.elapsed_time(e1) / n
+            out[name] = {"M": a.shape[0], "N": w.shape[0], "K": a.shape[1], "launches": n, "ms": ms,
+                         "TFLOP/s": flops / (ms * 1e-3) / 1e12,
+                         "frac_of_bf16_peak": flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+                         "sclk_MHz_median": mhz, "board_power_W_median": watts}
+            del a, w
+        print(json.dumps({"vendor_gemm_yardstick": out}), flush=True)
         return
     cfg = synth.PRESETS[args.workload]
     if args.tokens > 0:

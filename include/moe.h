@@ -269,7 +269,8 @@ int moe_estimate_streamed_stage(const moe_shape* shape, const int32_t* rows, int
  * the gathered rows x_perm to the workspace and run the gate/up GEMM on them (the path taken by
  * itself when T*d_model*2 bytes do not fit 32 bits) instead of reading token rows through the
  * permutation. Adding 128 keeps the 256-row tiles of a last round that is less than half full
- * whole (by default each is run as two 128-row halves). Every setting produces identical bits (same accumulation chain per
+ * whole (by default each is run as two 128-row halves). Adding 256 / 512 runs the 256-row tiles
+ * with eight wavefronts of 128 x 64 outputs / four of 128 x 128 (the default). Every setting produces identical bits (same accumulation chain per
  * output element); only speed differs. Returns MOE_ERR_INVALID_ARG for other values. */
 int moe_set_gemm_config(moe_ctx* ctx, int config);
 

@@ -48,6 +48,7 @@ struct GemmEnv {
     int stream_mode = -1;             // -1: automatic; 0: weights never non-temporal; 1: always
     bool materialise_gather = false;  // layer calls write x_perm instead of fusing the gather
     bool split_last_round = true;     // large tiles: halve the tiles of a last round under half full
+    int large_tile_waves = 0;         // 0: automatic; 4 / 8: wavefronts of the 256 x 256 tile
 };
 int launch_gateup(const GemmEnv& env, const moe_bf16* a, const int32_t* row_index, int index_div,
                   const int32_t* offsets, int R, int R_hint, int d, int f, int E,

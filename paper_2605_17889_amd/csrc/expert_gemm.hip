@@ -20,6 +20,7 @@ namespace {
 
 using gemm::Config;
 
+
 // Compute units of a device (rounds of the pipelined kernel are that many tiles long).
 int compute_units(int device) {
     static std::atomic<int> cached[64];
@@ -102,6 +103,14 @@ int pick_config(const GemmEnv& env, int R, int E) {
     return padded_large * 0.8 <= padded_mid ? 0 : 1;
 }
 
+// Large tiles: four wavefronts of 128 x 128 outputs (one per SIMD) or eight of 128 x 64. The
+// four-wavefront form addresses a weight row by a 32-bit byte offset from the expert's matrix.
+bool use_one_wave_per_simd(const GemmEnv& env, int N, int K) {
+    if (static_cast<unsigned long long>(N) * K * 2ull >= (1ull << 32)) return false;
+    if (env.large_tile_waves != 0) return env.large_tile_waves == 4;
+    return true;     // faster at every shape measured (reductions of 768 to 16384)
+}
+
 // Weights may be loaded as non-temporal when (almost) every expert has a single m-tile: then no
 // other tile asks for the same weight bytes and keeping them cached only displaces the rows.
 bool single_m_tile(const GemmEnv& env, int R, int E, int BM) {
@@ -112,6 +121,11 @@ bool single_m_tile(const GemmEnv& env, int R, int E, int BM) {
 
 //                      BM   BN  BK WM WN NSTAGE DUAL [STREAM_B]
 using GateUpLarge = Config<256, 256, 64, 2, 4, 2, true>;
+// one wavefront per SIMD: 2 x 2 wavefronts of 128 x 128 outputs; its half-height tile keeps 4 wavefronts
+using GateUpLarge1W = Config<256, 256, 64, 2, 2, 2, true>;
+using GateUpHalf1W  = Config<128, 256, 64, 1, 4, 3, true>;
+using DownLarge1W   = Config<256, 256, 64, 2, 2, 2, false>;
+using DownHalf1W    = Config<128, 256, 64, 1, 4, 3, false>;
 using GateUpMid   = Config<128, 256, 64, 2, 4, 3, true>;   // also the half-height tile of GateUpLarge
 using GateUpSmall = Config<64, 128, 64, 1, 2, 4, true>;
 using DownLarge   = Config<256, 256, 64, 2, 4, 2, false>;
@@ -145,7 +159,10 @@ int launch_gateup(const GemmEnv& env, const moe_bf16* a, const int32_t* row_inde
     int config = pick_config(env, R_hint, E);
     if (config == 0 && d / 64 < 3) config = 1;     // the pipelined kernel needs three k-steps
     switch (config) {
-        case 0: return launch_ring<GateUpLarge, GateUpMid, 2, 3>(env, x_perm, W1, W3, H, offsets, row_index, index_div, R, E, f, d, s);
+        case 0:
+            if (use_one_wave_per_simd(env, f, d))
+                return launch_ring<GateUpLarge1W, GateUpHalf1W, 2, 3>(env, x_perm, W1, W3, H, offsets, row_index, index_div, R, E, f, d, s);
+            return launch_ring<GateUpLarge, GateUpMid, 2, 3>(env, x_perm, W1, W3, H, offsets, row_index, index_div, R, E, f, d, s);
         case 1:
             if (single_m_tile(env, R_hint, E, 128))
                 return launch_grouped<GateUpMidS>(env, x_perm, W1, W3, H, offsets, row_index, index_div, R, E, f, d, s);
@@ -167,7 +184,10 @@ int launch_down(const GemmEnv& env, const moe_bf16* H, const int32_t* offsets, i
     int config = pick_config(env, R_hint, E);
     if (config == 0 && f / 64 < 3) config = 1;     // the pipelined kernel needs three k-steps
     switch (config) {
-        case 0: return launch_ring<DownLarge, DownMidWide, 2, 3>(env, H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
+        case 0:
+            if (use_one_wave_per_simd(env, d, f))
+                return launch_ring<DownLarge1W, DownHalf1W, 2, 3>(env, H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
+            return launch_ring<DownLarge, DownMidWide, 2, 3>(env, H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
         case 1:
             // HBM-bound: wide tiles stream more bytes per workgroup, but only if there are
             // enough of them to occupy the 256 compute units (about one m-tile per expert).

@@ -651,6 +651,242 @@ __device__ __forceinline__ void ring_tile(const TileCoord& tc, unsigned char* sm
     store_tile<Cfg>(acc, tc, fp, wm, wn, C, N);
 }
 
+// ---- the full tile with ONE wavefront per SIMD (4 wavefronts, 128 x 128 outputs each) --------
+// Four wavefronts read 128 KB of fragments from LDS per k-step where eight read 192 KB, and hold
+// all 256 accumulator registers of a lane's SIMD, so every fragment set can be double-buffered
+// in the other 256 registers. With a single wavefront per SIMD nothing covers for it: a wavefront
+// issues one instruction every four cycles, an MFMA occupies the matrix pipe for sixteen, so at
+// most three other instructions fit between two MFMAs before the pipe runs dry. The k-step below
+// therefore places every LDS read, every direct-to-LDS load and every scalar update behind an
+// MFMA of its own: per half-step of 64 MFMAs, 16 fragment reads (after every fourth MFMA), 8
+// loads (in every group of eight MFMAs: M0 is written before one MFMA and the load issued after
+// it, the MFMA serving as the wait state that a write to M0 needs) and the pointer updates.
+// The A loads of k-step kt+NA go out in the second half of k-step kt, the B loads of k-step
+// kt+NB in the first half of k-step kt+1, so the texture-address unit sees one load per SIMD
+// every 128 cycles throughout instead of all sixteen within one half.
+template <class Cfg>
+struct LoadPlan1W {
+    static constexpr int LA = Cfg::NIA / Cfg::NW, LB = Cfg::NIB / Cfg::NW;
+    const uint16_t* a_ptr;          // A origin + current k offset of the A loads
+    const uint16_t* b_ptr[2];       // expert's W (and W3 with DUAL) + current k offset of the B loads
+    uint32_t a_voff[LA], b_voff[LB];
+    uint32_t a_lds, b_lds;          // this wavefront's first load inside an A / B stage
+    __device__ __forceinline__ void init(const TileCoord& tc, int wave, int lane, const uint16_t* A,
+                                         const uint16_t* B0, const uint16_t* B1,
+                                         const int32_t* row_index, int index_div, int N, int K) {
+        const int lrow = lane / Cfg::CPR, lpos = lane % Cfg::CPR;
+        a_ptr = a_origin(A, tc, row_index, K);
+        const size_t expert_off = static_cast<size_t>(tc.expert) * N * K;
+        b_ptr[0] = B0 + expert_off;
+        b_ptr[1] = Cfg::DUAL ? B1 + expert_off : b_ptr[0];
+#pragma unroll
+        for (int i = 0; i < LA; ++i) {
+            const int r = (wave * LA + i) * Cfg::RPI + lrow;
+            const int src = source_row(tc, min(r, tc.rows - 1), row_index, index_div);
+            a_voff[i] = (static_cast<uint32_t>(src) * K + ((lpos ^ swz<Cfg::BK>(r)) * 8)) * 2u;
+        }
+#pragma unroll
+        for (int i = 0; i < LB; ++i) {
+            const int r0 = (wave * LB + i) * Cfg::RPI;          // first tile row of the load
+            const int col0 = tc.nt * Cfg::BN_OUT + (Cfg::DUAL ? (r0 >> 6) * 32 + (r0 & 31) : r0);
+            b_voff[i] = (static_cast<uint32_t>(col0 + lrow) * K + ((lpos ^ swz<Cfg::BK>(r0 + lrow)) * 8)) * 2u;
+        }
+        a_lds = wave * LA * 1024;
+        b_lds = wave * LB * 1024;
+    }
+    // weight matrix of B load i (W1 and W3 rows alternate in blocks of 32 tile rows)
+    __device__ __forceinline__ const uint16_t* b_src(int wave, int i) const {
+        return b_ptr[Cfg::DUAL ? (((wave * LB + i) * Cfg::RPI) >> 5) & 1 : 0];
+    }
+};
+
+// acc += W_frag * X_frag with the accumulator pinned to AGPRs; then one direct-to-LDS load whose
+// LDS address (lds_base + LDS_OFF) was put into M0 before the MFMA.
+template <int LDS_OFF>
+__device__ __forceinline__ void mma16_then_dma(const bf16x8& w, const bf16x8& x, f32x4& acc,
+                                               uint32_t lds_base, uint32_t voff, const void* sbase) {
+    asm volatile("s_add_u32 m0, %3, %4\n\t"
+                 "v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0\n\t"
+                 "global_load_lds_dwordx4 %5, %6"
+                 : "+a"(acc)
+                 : "v"(w), "v"(x), "s"(lds_base), "n"(LDS_OFF), "v"(voff), "s"(sbase)
+                 : "memory", "m0", "scc");
+}
+
+// One k-step of one wavefront. On entry f[0] holds the first-half fragments of this k-step.
+// Every k-step runs exactly this code, without a branch: the accumulators are operands of inline
+// assembly, which the compiler does not know to be MFMAs, so it must never find a reason (a join
+// of two paths, a second loop) to move them between registers next to one. The first half issues
+// the B loads of k-step kt-1+NB, the second half the A loads of k-step kt+NA. Past the end of the
+// reduction the pointers stop advancing: the loads of the last k-steps fetch the last 64 k again
+// into stages that nobody reads any more, which keeps the number of loads in flight, and with it
+// the load-counter value to wait for, the same in every k-step. Likewise the last k-step reads
+// "next" fragments from a stage that holds nothing new; they are never used.
+// LDS addresses of one k-step: fragment pointers of this k-step's second half (h1) and of the
+// next k-step's first half (n0), the stages that this k-step's loads refill, and the ring
+// positions (as byte offsets) they derive from.
+struct RingState1W {
+    const unsigned char *pa_h1, *pb_h1, *pa_n0, *pb_n0;
+    uint32_t a_region, b_region;    // M0 bases of the A loads (stage kt) / B loads (stage kt-1)
+    uint32_t sa, sb;                // byte offsets of k-step kt's stages inside the A / B ring
+};
+
+template <class Cfg, int NA, int NB>
+__device__ __forceinline__ void kstep_1w(f32x4 (&acc)[8][8], bf16x8 (&fa)[2][8], bf16x8 (&fb)[2][8],
+                                         RingState1W& rs, LoadPlan1W<Cfg>& lp, int wave,
+                                         const unsigned char* pa0, const unsigned char* pa1,
+                                         const unsigned char* pb0, const unsigned char* pb1, int kt,
+                                         int KT) {
+    using R = RingCfg<Cfg, NA, NB>;
+    constexpr int LA = LoadPlan1W<Cfg>::LA, LB = LoadPlan1W<Cfg>::LB;
+    constexpr uint32_t AB = Cfg::A_BYTES, BB = Cfg::B_BYTES;
+    static_assert(Cfg::TM == 8 && Cfg::TN == 8 && LA == 8 && LB == 8 && NA == 2, "128 x 128 per wavefront");
+    const uint32_t a_region = rs.a_region, b_region = rs.b_region;
+    const unsigned char *pa_h1 = rs.pa_h1, *pb_h1 = rs.pb_h1, *pa_n0 = rs.pa_n0, *pb_n0 = rs.pb_n0;
+    // ---- first half: MFMAs on f[0]; read f[1] (second half of this k-step); B loads
+#pragma unroll
+    for (int m = 0; m < 64; ++m) {
+        const int i = m >> 3, j = m & 7;
+        if ((m & 7) == 3) {
+            // the eight B loads of a wavefront: four rows-of-W1 loads, then four of W3 (DUAL)
+            const int n = m >> 3;
+            if (n == 0) mma16_then_dma<0 * 1024>(fb[0][j], fa[0][i], acc[i][j], b_region, lp.b_voff[0], lp.b_src(wave, 0));
+            if (n == 1) mma16_then_dma<1 * 1024>(fb[0][j], fa[0][i], acc[i][j], b_region, lp.b_voff[1], lp.b_src(wave, 1));
+            if (n == 2) mma16_then_dma<2 * 1024>(fb[0][j], fa[0][i], acc[i][j], b_region, lp.b_voff[2], lp.b_src(wave, 2));
+            if (n == 3) mma16_then_dma<3 * 1024>(fb[0][j], fa[0][i], acc[i][j], b_region, lp.b_voff[3], lp.b_src(wave, 3));
+            if (n == 4) mma16_then_dma<4 * 1024>(fb[0][j], fa[0][i], acc[i][j], b_region, lp.b_voff[4], lp.b_src(wave, 4));
+            if (n == 5) mma16_then_dma<5 * 1024>(fb[0][j], fa[0][i], acc[i][j], b_region, lp.b_voff[5], lp.b_src(wave, 5));
+            if (n == 6) mma16_then_dma<6 * 1024>(fb[0][j], fa[0][i], acc[i][j], b_region, lp.b_voff[6], lp.b_src(wave, 6));
+            if (n == 7) mma16_then_dma<7 * 1024>(fb[0][j], fa[0][i], acc[i][j], b_region, lp.b_voff[7], lp.b_src(wave, 7));
+        } else {
+            mma16_agpr(fb[0][j], fa[0][i], acc[i][j]);
+        }
+        MOE_FENCE();
+        if ((m & 3) == 0) {
+            const int r = m >> 2;                           // B fragments first: every MFMA row needs them
+            if (r < 8) fb[1][r] = lds16(pb_h1 + r * Cfg::TILE_STEP);
+            else fa[1][r - 8] = lds16(pa_h1 + (r - 8) * Cfg::TILE_STEP);
+            MOE_FENCE();
+        }
+        // the B pointers move on (behind the last B load) while a later k-step exists
+        if (m == 61) { lp.b_ptr[0] += (kt + NB < KT) ? Cfg::BK : 0; MOE_FENCE(); }
+        if (m == 62 && Cfg::DUAL) { lp.b_ptr[1] += (kt + NB < KT) ? Cfg::BK : 0; MOE_FENCE(); }
+    }
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" :: "n"(LB) : "memory");
+    __builtin_amdgcn_s_barrier();      // k-step kt+1 complete in LDS; this k-step's stages are free
+    MOE_FENCE();
+    // ---- second half: MFMAs on f[1]; read f[0] of k-step kt+1; A loads; the next k-step's ring
+    //      addresses, one small step behind an MFMA at a time
+    uint32_t sb1 = 0, sb2 = 0, sa1 = 0;
+    RingState1W nx;
+#pragma unroll
+    for (int m = 0; m < 64; ++m) {
+        const int i = m >> 3, j = m & 7;
+        if ((m & 7) == 3) {
+            const int n = m >> 3;
+            if (n == 0) mma16_then_dma<0 * 1024>(fb[1][j], fa[1][i], acc[i][j], a_region, lp.a_voff[0], lp.a_ptr);
+            if (n == 1) mma16_then_dma<1 * 1024>(fb[1][j], fa[1][i], acc[i][j], a_region, lp.a_voff[1], lp.a_ptr);
+            if (n == 2) mma16_then_dma<2 * 1024>(fb[1][j], fa[1][i], acc[i][j], a_region, lp.a_voff[2], lp.a_ptr);
+            if (n == 3) mma16_then_dma<3 * 1024>(fb[1][j], fa[1][i], acc[i][j], a_region, lp.a_voff[3], lp.a_ptr);
+            if (n == 4) mma16_then_dma<4 * 1024>(fb[1][j], fa[1][i], acc[i][j], a_region, lp.a_voff[4], lp.a_ptr);
+            if (n == 5) mma16_then_dma<5 * 1024>(fb[1][j], fa[1][i], acc[i][j], a_region, lp.a_voff[5], lp.a_ptr);
+            if (n == 6) mma16_then_dma<6 * 1024>(fb[1][j], fa[1][i], acc[i][j], a_region, lp.a_voff[6], lp.a_ptr);
+            if (n == 7) mma16_then_dma<7 * 1024>(fb[1][j], fa[1][i], acc[i][j], a_region, lp.a_voff[7], lp.a_ptr);
+        } else {
+            mma16_agpr(fb[1][j], fa[1][i], acc[i][j]);
+        }
+        MOE_FENCE();
+        if ((m & 3) == 0) {
+            const int r = m >> 2;
+            if (r < 8) fb[0][r] = lds16(pb_n0 + r * Cfg::TILE_STEP);
+            else fa[0][r - 8] = lds16(pa_n0 + (r - 8) * Cfg::TILE_STEP);
+            MOE_FENCE();
+        }
+        if (m == 1) { sb1 = rs.sb + BB; MOE_FENCE(); }
+        if (m == 2) { sb1 = (sb1 == NB * BB) ? 0u : sb1; MOE_FENCE(); }                 // stage of k-step kt+1
+        if (m == 5) { sb2 = sb1 + BB; MOE_FENCE(); }
+        if (m == 6) { sb2 = (sb2 == NB * BB) ? 0u : sb2; MOE_FENCE(); }                 // ... of kt+2
+        if (m == 9) { sa1 = rs.sa ^ AB; MOE_FENCE(); }                                  // two A stages
+        if (m == 10) { nx.pa_h1 = pa1 + sa1; MOE_FENCE(); }
+        if (m == 13) { nx.pb_h1 = pb1 + sb1; MOE_FENCE(); }
+        if (m == 14) { nx.pa_n0 = pa0 + rs.sa; MOE_FENCE(); }
+        if (m == 17) { nx.pb_n0 = pb0 + sb2; MOE_FENCE(); }
+        if (m == 18) { nx.a_region = sa1 + lp.a_lds; MOE_FENCE(); }
+        if (m == 21) { nx.b_region = R::A_RING + rs.sb + lp.b_lds; MOE_FENCE(); }
+        if (m == 61) { lp.a_ptr += (kt + NA + 1 < KT) ? Cfg::BK : 0; MOE_FENCE(); }
+    }
+    nx.sa = sa1;
+    nx.sb = sb1;
+    rs = nx;
+}
+
+template <class Cfg, int NA, int NB>
+__device__ __forceinline__ void ring_tile_1w(const TileCoord& tc, unsigned char* smem,
+                                             const uint16_t* __restrict__ A,
+                                             const uint16_t* __restrict__ B0,
+                                             const uint16_t* __restrict__ B1, uint16_t* __restrict__ C,
+                                             const int32_t* __restrict__ row_index, int index_div,
+                                             int N, int K) {
+    using R = RingCfg<Cfg, NA, NB>;
+    constexpr int BK = Cfg::BK, WN = Cfg::WN, TM = Cfg::TM, TN = Cfg::TN;
+    constexpr int LA = R::LA, LB = R::LB, AB = Cfg::A_BYTES, BB = Cfg::B_BYTES;
+    static_assert(BK == 64 && NA == 2 && NB == 3, "rings of 2 + 3 stages of 64 k");
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WN, wn = wave % WN;
+
+    LoadPlan1W<Cfg> lp;
+    lp.init(tc, wave, lane, A, B0, B1, row_index, index_div, N, K);
+    FragPlan<Cfg> fp;
+    fp.init(lane, wm, wn);
+    const unsigned char* pa[2] = {smem + fp.a_off[0], smem + fp.a_off[1]};
+    const unsigned char* pb[2] = {smem + R::A_RING + (fp.b_off[0] - AB), smem + R::A_RING + (fp.b_off[1] - AB)};
+
+    f32x4 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    mfma_drain();                                    // accumulator writes settle before MFMAs
+
+    const int KT = K / BK;                           // >= NB (checked by the launcher)
+    // prologue: A stages 0..NA-1 and B stages 0..NB-2, in the order the k-loop issues them; the
+    // first half of k-step 0 adds B stage NB-1 like any other k-step
+#pragma unroll
+    for (int s = 0; s < NA; ++s) {
+#pragma unroll
+        for (int i = 0; i < LA; ++i) dma16(lp.a_ptr, lp.a_voff[i], s * AB + lp.a_lds + i * 1024);
+        lp.a_ptr += BK;
+        if (s < NB - 1) {
+#pragma unroll
+            for (int i = 0; i < LB; ++i)
+                dma16(lp.b_src(wave, i), lp.b_voff[i], R::A_RING + s * BB + lp.b_lds + i * 1024);
+            lp.b_ptr[0] += BK;
+            if (Cfg::DUAL) lp.b_ptr[1] += BK;
+        }
+    }
+    static_assert(NB - 1 == NA, "prologue order");
+    wait_vmcnt<(NA - 1) * (LA + LB)>();              // k-step 0 landed
+    __builtin_amdgcn_s_barrier();
+    bf16x8 fa[2][TM], fb[2][TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) fb[0][j] = lds16(pb[0] + j * Cfg::TILE_STEP);
+#pragma unroll
+    for (int i = 0; i < TM; ++i) fa[0][i] = lds16(pa[0] + i * Cfg::TILE_STEP);
+    MOE_FENCE();
+
+    // k-step 0: stages 0; its B loads refill the stage "before" it, NB-1, which is still empty
+    RingState1W rs{pa[1], pb[1], pa[0] + AB, pb[0] + BB, lp.a_lds,
+                   R::A_RING + (NB - 1) * BB + lp.b_lds, 0u, 0u};
+    for (int kt = 0; kt < KT; ++kt)
+        kstep_1w<Cfg, NA, NB>(acc, fa, fb, rs, lp, wave, pa[0], pa[1], pb[0], pb[1], kt, KT);
+    wait_vmcnt<0>();                                 // the refills of the last k-steps, never read
+    mfma_drain();
+    store_tile<Cfg>(acc, tc, fp, wm, wn, C, N);
+}
+
 // Tiles are enumerated at Cfg::BM rows. A tile that holds at most HalfCfg::BM = Cfg::BM / 2 rows
 // (an expert's short tail, or a half of a tile of the last, partial round: see locate_tile) runs
 // the same pipeline at half height: it issues half the MFMAs and A loads, and takes about 0.6 of
@@ -671,6 +907,8 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void grouped_gemm_ring_kernel(
     if (tc.expert < 0) return;                       // uniform for the whole workgroup
     if (tc.rows <= HalfCfg::BM)
         ring_tile<HalfCfg, NA, NB>(tc, smem, A, B0, B1, C, row_index, index_div, N, K);
+    else if constexpr (Cfg::NW == 4)
+        ring_tile_1w<Cfg, NA, NB>(tc, smem, A, B0, B1, C, row_index, index_div, N, K);
     else
         ring_tile<Cfg, NA, NB>(tc, smem, A, B0, B1, C, row_index, index_div, N, K);
 }

@@ -487,11 +487,15 @@ int moe_profile_end(moe_ctx* c, double* stage_ms, int64_t* stage_launches, int32
  * 2 small, 3 tiny rows-per-expert), or -1 for the automatic choice; +16 never loads weights as
  * non-temporal, +32 always does (medium and small tiles); +64 makes the layer calls write the
  * gathered rows to the workspace instead of reading them through the permutation; +128 keeps the
- * large tiles of a last, partial round whole. All settings give identical bits. */
+ * large tiles of a last, partial round whole; +256 / +512 run the large tiles with eight / four
+ * wavefronts. All settings give identical bits. */
 int moe_set_gemm_config(moe_ctx* c, int config) {
     if (!c) return MOE_ERR_INVALID_ARG;
     int stream_mode = -1;
     bool materialise = false, split = true;
+    int large_waves = 0;
+    if (config >= 511) { large_waves = 4; config -= 512; }
+    else if (config >= 255) { large_waves = 8; config -= 256; }
     if (config >= 127) { split = false; config -= 128; }
     if (config >= 63) { materialise = true; config -= 64; }
     if (config >= 31) { stream_mode = 1; config -= 32; }
@@ -499,6 +503,7 @@ int moe_set_gemm_config(moe_ctx* c, int config) {
     if (config < -1 || config > 3) return MOE_ERR_INVALID_ARG;
     c->gemm.materialise_gather = materialise;
     c->gemm.split_last_round = split;
+    c->gemm.large_tile_waves = large_waves;
     c->gemm.forced_config = config;
     c->gemm.stream_mode = stream_mode;
     return MOE_OK;

@@ -213,8 +213,8 @@ __global__ __launch_bounds__(256) void route_select_kernel(const float* __restri
 // needs is staged once per workgroup in LDS (coalesced 16-byte global reads) and every lane
 // then pulls its own 8 x E weights with 16-byte LDS reads. Lane l's 8*E floats sit at byte
 // offset l * (32*E + 16): the 16-byte pad spreads 16 consecutive lanes over all 64 banks.
-template <int E_, int TOK>
-__global__ __launch_bounds__(256) void route_kernel_lds(const uint16_t* __restrict__ x,
+template <int E_, int TOK, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void route_kernel_lds(const uint16_t* __restrict__ x,
                                                         const float* __restrict__ wr,
                                                         const float* __restrict__ bias, int T,
                                                         int d, int k,
@@ -224,12 +224,14 @@ __global__ __launch_bounds__(256) void route_kernel_lds(const uint16_t* __restri
     constexpr int E = E_;
     constexpr int LANE_BYTES = 32 * E + 16;             // padded per-lane slice
     constexpr int CHUNK_BYTES = 512 * E * 4;            // W_r bytes per 512-element chunk
-    constexpr int VEC_PER_THREAD = CHUNK_BYTES / 16 / 256;
+    constexpr int NTHR = WAVES * 64;
+    constexpr int VEC_PER_THREAD = CHUNK_BYTES / 16 / NTHR;
+    static_assert(VEC_PER_THREAD >= 1 && VEC_PER_THREAD * NTHR * 16 == CHUNK_BYTES, "staging split");
     __shared__ __attribute__((aligned(16))) unsigned char wlds[2][64 * LANE_BYTES];
 
     const int lane = threadIdx.x & (kWave - 1);
     const int wave_in_block = threadIdx.x / kWave;
-    const int t0 = (blockIdx.x * 4 + wave_in_block) * TOK;
+    const int t0 = (blockIdx.x * WAVES + wave_in_block) * TOK;
 
     float acc[TOK][E];
 #pragma unroll
@@ -242,12 +244,12 @@ __global__ __launch_bounds__(256) void route_kernel_lds(const uint16_t* __restri
     auto load_w = [&](int j) {
         const u32x4* src = reinterpret_cast<const u32x4*>(wr + static_cast<size_t>(j) * 512 * E);
 #pragma unroll
-        for (int i = 0; i < VEC_PER_THREAD; ++i) stage[i] = src[threadIdx.x + i * 256];
+        for (int i = 0; i < VEC_PER_THREAD; ++i) stage[i] = src[threadIdx.x + i * NTHR];
     };
     auto store_w = [&](int buf) {
 #pragma unroll
         for (int i = 0; i < VEC_PER_THREAD; ++i) {
-            const int byte = (threadIdx.x + i * 256) * 16;          // offset inside the chunk
+            const int byte = (threadIdx.x + i * NTHR) * 16;          // offset inside the chunk
             const int l = byte / (32 * E), within = byte % (32 * E);
             *reinterpret_cast<u32x4*>(&wlds[buf][l * LANE_BYTES + within]) = stage[i];
         }
@@ -449,11 +451,11 @@ __global__ __launch_bounds__(256, 2) void route_logits_group_kernel(const uint16
             bias != nullptr ? acc[0] + bias[e0 + e] : acc[0];
 }
 
-template <int E_, int TOK>
+template <int E_, int TOK, int WAVES>
 int launch_route_lds(const moe_bf16* x, const float* wr, const float* bias, int T, int d, int k,
                      int32_t* idx, float* w, float* logits_out, hipStream_t s) {
-    const int blocks = (T + 4 * TOK - 1) / (4 * TOK);
-    hipLaunchKernelGGL((route_kernel_lds<E_, TOK>), dim3(blocks), dim3(256), 0, s, x, wr, bias, T, d,
+    const int blocks = (T + WAVES * TOK - 1) / (WAVES * TOK);
+    hipLaunchKernelGGL((route_kernel_lds<E_, TOK, WAVES>), dim3(blocks), dim3(WAVES * 64), 0, s, x, wr, bias, T, d,
                        k, idx, w, logits_out);
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
@@ -513,8 +515,9 @@ int launch_route(const moe_bf16* x, const float* w_router, const float* bias, in
         if (hipGetLastError() != hipSuccess) return MOE_ERR_HIP;
         return launch_route_from_logits(logits, T, E, k, topk_idx, topk_w, s);
     }
-    if (E == 8) return launch_route_lds<8, 2>(x, w_router, bias, T, d, k, topk_idx, topk_w, logits_out, s);
-    if (E == 16) return launch_route_lds<16, 2>(x, w_router, bias, T, d, k, topk_idx, topk_w, logits_out, s);
+    // 8 wavefronts share one staged slice of W_r: half the staging work per token of 4-wave blocks
+    if (E == 8) return launch_route_lds<8, 2, 8>(x, w_router, bias, T, d, k, topk_idx, topk_w, logits_out, s);
+    if (E == 16) return launch_route_lds<16, 2, 8>(x, w_router, bias, T, d, k, topk_idx, topk_w, logits_out, s);
     if (E <= 8) return launch_route_t<8, 4>(x, w_router, bias, T, d, E, k, topk_idx, topk_w, logits_out, s);
     return launch_route_t<16, 2>(x, w_router, bias, T, d, E, k, topk_idx, topk_w, logits_out, s);
 }

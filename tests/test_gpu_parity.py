@@ -211,7 +211,7 @@ def test_permute_bit_exact(T, E, k, seed, empty):
 
 
 # ---------------------------------------------------------------- expert FFN and combine
-@pytest.mark.parametrize("config", [0, 0 + 128, 1, 2, 3, 2 + 16, 3 + 32])   # +16 / +32: cached / non-temporal weights
+@pytest.mark.parametrize("config", [0, 0 + 128, 0 + 256, 0 + 512, 1, 2, 3, 2 + 16, 3 + 32])   # +16 / +32: cached / non-temporal weights
 @pytest.mark.parametrize("d,f,rows", [
     (512, 256, [300, 0, 1, 77]),          # empty expert, single row, ragged tails
     (512, 512, [256, 257, 64, 31, 0, 5, 128, 129]),
@@ -243,7 +243,7 @@ def test_expert_ffn_parity(config, d, f, rows):
     ctx.close()
 
 
-ALL_TILE_CONFIGS = [0, 1, 2, 3]
+ALL_TILE_CONFIGS = [0 + 256, 0 + 512, 1, 2, 3]
 
 
 @pytest.mark.parametrize("config", ALL_TILE_CONFIGS)
@@ -302,7 +302,7 @@ def test_expert_ffn_configs_agree_bitwise():
     ctx = B.MoeContext(R, d, f, E, 1)
     outs = []
     try:
-        for config in (0, 0 + 128, 1, 2, 3, 1 + 32, 3 + 16):
+        for config in (0, 0 + 128, 0 + 256, 0 + 512, 0 + 512 + 128, 1, 2, 3, 1 + 32, 3 + 16):
             B.moe_set_gemm_config(ctx, config)
             yp = torch.empty((R, d), dtype=torch.bfloat16, device="cuda")
             B.moe_expert_ffn(ctx, xp, dev(offsets), R, W1, W3, W2, yp)
@@ -440,10 +440,10 @@ def test_layer_tiny_ragged_T(T):
 def test_gemm_config_values():
     """The tuning knob belongs to one context and validates its argument."""
     ctx = B.MoeContext(16, 512, 256, 8, 2)
-    for bad in (9, 4 + 32, 4 + 64, 4 + 128, -2):
+    for bad in (9, 4 + 32, 4 + 64, 4 + 128, 4 + 256, 4 + 512, -2):
         with pytest.raises(B.MoeError):
             B.moe_set_gemm_config(ctx, bad)
-    for ok in (0, 3, 1 + 16, -1 + 32, -1 + 64, 2 + 32 + 64, -1 + 128, 0 + 128 + 64, -1):
+    for ok in (0, 3, 1 + 16, -1 + 32, -1 + 64, 2 + 32 + 64, -1 + 128, 0 + 128 + 64, -1 + 256, -1 + 512, 0 + 512 + 128 + 64, -1):
         B.moe_set_gemm_config(ctx, ok)
     ctx.close()
 
