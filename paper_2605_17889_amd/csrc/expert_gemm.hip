@@ -121,11 +121,11 @@ bool single_m_tile(const GemmEnv& env, int R, int E, int BM) {
 
 //                      BM   BN  BK WM WN NSTAGE DUAL [STREAM_B]
 using GateUpLarge = Config<256, 256, 64, 2, 4, 2, true>;
-// one wavefront per SIMD: 2 x 2 wavefronts of 128 x 128 outputs; its half-height tile keeps 4 wavefronts
+// one wavefront per SIMD: 2 x 2 wavefronts of 128 x 128 outputs, or of 64 x 128 at half height
 using GateUpLarge1W = Config<256, 256, 64, 2, 2, 2, true>;
-using GateUpHalf1W  = Config<128, 256, 64, 1, 4, 3, true>;
+using GateUpHalf1W  = Config<128, 256, 64, 2, 2, 3, true>;
 using DownLarge1W   = Config<256, 256, 64, 2, 2, 2, false>;
-using DownHalf1W    = Config<128, 256, 64, 1, 4, 3, false>;
+using DownHalf1W    = Config<128, 256, 64, 2, 2, 3, false>;
 using GateUpMid   = Config<128, 256, 64, 2, 4, 3, true>;   // also the half-height tile of GateUpLarge
 using GateUpSmall = Config<64, 128, 64, 1, 2, 4, true>;
 using DownLarge   = Config<256, 256, 64, 2, 4, 2, false>;

@@ -651,6 +651,15 @@ __device__ __forceinline__ void ring_tile(const TileCoord& tc, unsigned char* sm
     store_tile<Cfg>(acc, tc, fp, wm, wn, C, N);
 }
 
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>) in order
+template <int N, int I = 0, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<N, I + 1>(f);
+    }
+}
+
 // ---- the full tile with ONE wavefront per SIMD (4 wavefronts, 128 x 128 outputs each) --------
 // Four wavefronts read 128 KB of fragments from LDS per k-step where eight read 192 KB, and hold
 // all 256 accumulator registers of a lane's SIMD, so every fragment set can be double-buffered
@@ -731,90 +740,87 @@ struct RingState1W {
     uint32_t sa, sb;                // byte offsets of k-step kt's stages inside the A / B ring
 };
 
+// MFMA number m of a half-step with its load, if it has one: load n = m / STRIDE goes out behind
+// MFMA m when m % STRIDE == 3 and n < NLOADS.
+template <int M, int STRIDE, int NLOADS>
+__device__ __forceinline__ void mma16_slot(const bf16x8& w, const bf16x8& x, f32x4& acc,
+                                           uint32_t lds_base, const uint32_t* voff,
+                                           const void* sbase) {
+    if constexpr (M % STRIDE == 3 && M / STRIDE < NLOADS)
+        mma16_then_dma<(M / STRIDE) * 1024>(w, x, acc, lds_base, voff[M / STRIDE], sbase);
+    else
+        mma16_agpr(w, x, acc);
+}
+
 template <class Cfg, int NA, int NB>
-__device__ __forceinline__ void kstep_1w(f32x4 (&acc)[8][8], bf16x8 (&fa)[2][8], bf16x8 (&fb)[2][8],
-                                         RingState1W& rs, LoadPlan1W<Cfg>& lp, int wave,
-                                         const unsigned char* pa0, const unsigned char* pa1,
+__device__ __forceinline__ void kstep_1w(f32x4 (&acc)[Cfg::TM][8], bf16x8 (&fa)[2][Cfg::TM],
+                                         bf16x8 (&fb)[2][8], RingState1W& rs, LoadPlan1W<Cfg>& lp,
+                                         int wave, const unsigned char* pa0, const unsigned char* pa1,
                                          const unsigned char* pb0, const unsigned char* pb1, int kt,
                                          int KT) {
     using R = RingCfg<Cfg, NA, NB>;
+    constexpr int TM = Cfg::TM, NM = TM * 8, NR = TM + 8;      // MFMAs and fragment reads per half
     constexpr int LA = LoadPlan1W<Cfg>::LA, LB = LoadPlan1W<Cfg>::LB;
     constexpr uint32_t AB = Cfg::A_BYTES, BB = Cfg::B_BYTES;
-    static_assert(Cfg::TM == 8 && Cfg::TN == 8 && LA == 8 && LB == 8 && NA == 2, "128 x 128 per wavefront");
+    static_assert((TM == 8 || TM == 4) && Cfg::TN == 8 && LA == TM && LB == 8 && NA == 2,
+                  "128 or 64 rows x 128 columns per wavefront");
     const uint32_t a_region = rs.a_region, b_region = rs.b_region;
     const unsigned char *pa_h1 = rs.pa_h1, *pb_h1 = rs.pb_h1, *pa_n0 = rs.pa_n0, *pb_n0 = rs.pb_n0;
-    // ---- first half: MFMAs on f[0]; read f[1] (second half of this k-step); B loads
-#pragma unroll
-    for (int m = 0; m < 64; ++m) {
-        const int i = m >> 3, j = m & 7;
-        if ((m & 7) == 3) {
-            // the eight B loads of a wavefront: four rows-of-W1 loads, then four of W3 (DUAL)
-            const int n = m >> 3;
-            if (n == 0) mma16_then_dma<0 * 1024>(fb[0][j], fa[0][i], acc[i][j], b_region, lp.b_voff[0], lp.b_src(wave, 0));
-            if (n == 1) mma16_then_dma<1 * 1024>(fb[0][j], fa[0][i], acc[i][j], b_region, lp.b_voff[1], lp.b_src(wave, 1));
-            if (n == 2) mma16_then_dma<2 * 1024>(fb[0][j], fa[0][i], acc[i][j], b_region, lp.b_voff[2], lp.b_src(wave, 2));
-            if (n == 3) mma16_then_dma<3 * 1024>(fb[0][j], fa[0][i], acc[i][j], b_region, lp.b_voff[3], lp.b_src(wave, 3));
-            if (n == 4) mma16_then_dma<4 * 1024>(fb[0][j], fa[0][i], acc[i][j], b_region, lp.b_voff[4], lp.b_src(wave, 4));
-            if (n == 5) mma16_then_dma<5 * 1024>(fb[0][j], fa[0][i], acc[i][j], b_region, lp.b_voff[5], lp.b_src(wave, 5));
-            if (n == 6) mma16_then_dma<6 * 1024>(fb[0][j], fa[0][i], acc[i][j], b_region, lp.b_voff[6], lp.b_src(wave, 6));
-            if (n == 7) mma16_then_dma<7 * 1024>(fb[0][j], fa[0][i], acc[i][j], b_region, lp.b_voff[7], lp.b_src(wave, 7));
-        } else {
-            mma16_agpr(fb[0][j], fa[0][i], acc[i][j]);
-        }
-        MOE_FENCE();
-        if ((m & 3) == 0) {
-            const int r = m >> 2;                           // B fragments first: every MFMA row needs them
-            if (r < 8) fb[1][r] = lds16(pb_h1 + r * Cfg::TILE_STEP);
-            else fa[1][r - 8] = lds16(pa_h1 + (r - 8) * Cfg::TILE_STEP);
+    // fragment read r of a half goes out behind MFMA r * NM / NR: B fragments first (every MFMA
+    // row needs all of them), then the A fragments in the order the MFMA rows use them
+    auto read_behind = [&](auto mtag, bf16x8 (&dfb)[8], bf16x8 (&dfa)[TM], const unsigned char* pbq,
+                           const unsigned char* paq) {
+        constexpr int m = decltype(mtag)::value;
+        constexpr int r = (m * NR + NM - 1) / NM;               // first read index with r * NM / NR >= m
+        if constexpr (r < NR && (r * NM) / NR == m) {
+            if constexpr (r < 8) dfb[r] = lds16(pbq + r * Cfg::TILE_STEP);
+            else dfa[r - 8] = lds16(paq + (r - 8) * Cfg::TILE_STEP);
             MOE_FENCE();
         }
-        // the B pointers move on (behind the last B load) while a later k-step exists
-        if (m == 61) { lp.b_ptr[0] += (kt + NB < KT) ? Cfg::BK : 0; MOE_FENCE(); }
-        if (m == 62 && Cfg::DUAL) { lp.b_ptr[1] += (kt + NB < KT) ? Cfg::BK : 0; MOE_FENCE(); }
-    }
+    };
+    // ---- first half: MFMAs on f[0]; read f[1] (second half of this k-step); the eight B loads
+    //      (with DUAL: four loads of W1 rows, then four of W3 rows)
+    auto first = [&](auto mtag) {
+        constexpr int m = decltype(mtag)::value, i = m >> 3, j = m & 7, n = m / (NM / 8);
+        const void* src = lp.b_src(wave, n < 8 ? n : 0);
+        mma16_slot<m, NM / 8, 8>(fb[0][j], fa[0][i], acc[i][j], b_region, lp.b_voff, src);
+        MOE_FENCE();
+        read_behind(mtag, fb[1], fa[1], pb_h1, pa_h1);
+        // the B pointers move on behind the last B load (MFMA 7 * NM / 8 + 3) while a later k-step exists
+        constexpr int after_loads = 7 * (NM / 8) + 4;
+        if constexpr (m == (after_loads < NM ? after_loads + 1 : NM - 1)) {
+            lp.b_ptr[0] += (kt + NB < KT) ? Cfg::BK : 0;
+            if (Cfg::DUAL) lp.b_ptr[1] += (kt + NB < KT) ? Cfg::BK : 0;
+            MOE_FENCE();
+        }
+    };
+    // ---- second half: MFMAs on f[1]; read f[0] of k-step kt+1; the A loads; the next k-step's
+    //      ring addresses, one small step behind an MFMA at a time
+    uint32_t sb1 = 0, sb2 = 0, sa1 = 0;
+    RingState1W nx;
+    auto second = [&](auto mtag) {
+        constexpr int m = decltype(mtag)::value, i = m >> 3, j = m & 7;
+        mma16_slot<m, 8, LA>(fb[1][j], fa[1][i], acc[i][j], a_region, lp.a_voff, lp.a_ptr);
+        MOE_FENCE();
+        read_behind(mtag, fb[0], fa[0], pb_n0, pa_n0);
+        if constexpr (m == 1) { sb1 = rs.sb + BB; MOE_FENCE(); }
+        if constexpr (m == 2) { sb1 = (sb1 == NB * BB) ? 0u : sb1; MOE_FENCE(); }        // stage of k-step kt+1
+        if constexpr (m == 5) { sb2 = sb1 + BB; MOE_FENCE(); }
+        if constexpr (m == 6) { sb2 = (sb2 == NB * BB) ? 0u : sb2; MOE_FENCE(); }        // ... of kt+2
+        if constexpr (m == 9) { sa1 = rs.sa ^ AB; MOE_FENCE(); }                         // two A stages
+        if constexpr (m == 10) { nx.pa_h1 = pa1 + sa1; MOE_FENCE(); }
+        if constexpr (m == 13) { nx.pb_h1 = pb1 + sb1; MOE_FENCE(); }
+        if constexpr (m == 14) { nx.pa_n0 = pa0 + rs.sa; MOE_FENCE(); }
+        if constexpr (m == 17) { nx.pb_n0 = pb0 + sb2; MOE_FENCE(); }
+        if constexpr (m == 18) { nx.a_region = sa1 + lp.a_lds; MOE_FENCE(); }
+        if constexpr (m == 21) { nx.b_region = R::A_RING + rs.sb + lp.b_lds; MOE_FENCE(); }
+        if constexpr (m == NM - 3) { lp.a_ptr += (kt + NA + 1 < KT) ? Cfg::BK : 0; MOE_FENCE(); }
+    };
+    static_for<NM>(first);
     asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" :: "n"(LB) : "memory");
     __builtin_amdgcn_s_barrier();      // k-step kt+1 complete in LDS; this k-step's stages are free
     MOE_FENCE();
-    // ---- second half: MFMAs on f[1]; read f[0] of k-step kt+1; A loads; the next k-step's ring
-    //      addresses, one small step behind an MFMA at a time
-    uint32_t sb1 = 0, sb2 = 0, sa1 = 0;
-    RingState1W nx;
-#pragma unroll
-    for (int m = 0; m < 64; ++m) {
-        const int i = m >> 3, j = m & 7;
-        if ((m & 7) == 3) {
-            const int n = m >> 3;
-            if (n == 0) mma16_then_dma<0 * 1024>(fb[1][j], fa[1][i], acc[i][j], a_region, lp.a_voff[0], lp.a_ptr);
-            if (n == 1) mma16_then_dma<1 * 1024>(fb[1][j], fa[1][i], acc[i][j], a_region, lp.a_voff[1], lp.a_ptr);
-            if (n == 2) mma16_then_dma<2 * 1024>(fb[1][j], fa[1][i], acc[i][j], a_region, lp.a_voff[2], lp.a_ptr);
-            if (n == 3) mma16_then_dma<3 * 1024>(fb[1][j], fa[1][i], acc[i][j], a_region, lp.a_voff[3], lp.a_ptr);
-            if (n == 4) mma16_then_dma<4 * 1024>(fb[1][j], fa[1][i], acc[i][j], a_region, lp.a_voff[4], lp.a_ptr);
-            if (n == 5) mma16_then_dma<5 * 1024>(fb[1][j], fa[1][i], acc[i][j], a_region, lp.a_voff[5], lp.a_ptr);
-            if (n == 6) mma16_then_dma<6 * 1024>(fb[1][j], fa[1][i], acc[i][j], a_region, lp.a_voff[6], lp.a_ptr);
-            if (n == 7) mma16_then_dma<7 * 1024>(fb[1][j], fa[1][i], acc[i][j], a_region, lp.a_voff[7], lp.a_ptr);
-        } else {
-            mma16_agpr(fb[1][j], fa[1][i], acc[i][j]);
-        }
-        MOE_FENCE();
-        if ((m & 3) == 0) {
-            const int r = m >> 2;
-            if (r < 8) fb[0][r] = lds16(pb_n0 + r * Cfg::TILE_STEP);
-            else fa[0][r - 8] = lds16(pa_n0 + (r - 8) * Cfg::TILE_STEP);
-            MOE_FENCE();
-        }
-        if (m == 1) { sb1 = rs.sb + BB; MOE_FENCE(); }
-        if (m == 2) { sb1 = (sb1 == NB * BB) ? 0u : sb1; MOE_FENCE(); }                 // stage of k-step kt+1
-        if (m == 5) { sb2 = sb1 + BB; MOE_FENCE(); }
-        if (m == 6) { sb2 = (sb2 == NB * BB) ? 0u : sb2; MOE_FENCE(); }                 // ... of kt+2
-        if (m == 9) { sa1 = rs.sa ^ AB; MOE_FENCE(); }                                  // two A stages
-        if (m == 10) { nx.pa_h1 = pa1 + sa1; MOE_FENCE(); }
-        if (m == 13) { nx.pb_h1 = pb1 + sb1; MOE_FENCE(); }
-        if (m == 14) { nx.pa_n0 = pa0 + rs.sa; MOE_FENCE(); }
-        if (m == 17) { nx.pb_n0 = pb0 + sb2; MOE_FENCE(); }
-        if (m == 18) { nx.a_region = sa1 + lp.a_lds; MOE_FENCE(); }
-        if (m == 21) { nx.b_region = R::A_RING + rs.sb + lp.b_lds; MOE_FENCE(); }
-        if (m == 61) { lp.a_ptr += (kt + NA + 1 < KT) ? Cfg::BK : 0; MOE_FENCE(); }
-    }
+    static_for<NM>(second);
     nx.sa = sa1;
     nx.sb = sb1;
     rs = nx;
@@ -830,7 +836,7 @@ __device__ __forceinline__ void ring_tile_1w(const TileCoord& tc, unsigned char*
     using R = RingCfg<Cfg, NA, NB>;
     constexpr int BK = Cfg::BK, WN = Cfg::WN, TM = Cfg::TM, TN = Cfg::TN;
     constexpr int LA = R::LA, LB = R::LB, AB = Cfg::A_BYTES, BB = Cfg::B_BYTES;
-    static_assert(BK == 64 && NA == 2 && NB == 3, "rings of 2 + 3 stages of 64 k");
+    static_assert(BK == 64 && NA == 2 && NB == 3 && TN == 8, "rings of 2 + 3 stages of 64 k");
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -905,12 +911,18 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void grouped_gemm_ring_kernel(
 
     const TileCoord tc = locate_tile<Cfg::BM>(offsets, E, N / Cfg::BN_OUT, split_cus);
     if (tc.expert < 0) return;                       // uniform for the whole workgroup
-    if (tc.rows <= HalfCfg::BM)
-        ring_tile<HalfCfg, NA, NB>(tc, smem, A, B0, B1, C, row_index, index_div, N, K);
-    else if constexpr (Cfg::NW == 4)
-        ring_tile_1w<Cfg, NA, NB>(tc, smem, A, B0, B1, C, row_index, index_div, N, K);
-    else
-        ring_tile<Cfg, NA, NB>(tc, smem, A, B0, B1, C, row_index, index_div, N, K);
+    // four wavefronts of (128 or 64) x 128 outputs run the one-wavefront-per-SIMD pipeline
+    if (tc.rows <= HalfCfg::BM) {
+        if constexpr (HalfCfg::NW == 4 && HalfCfg::TN == 8)
+            ring_tile_1w<HalfCfg, NA, NB>(tc, smem, A, B0, B1, C, row_index, index_div, N, K);
+        else
+            ring_tile<HalfCfg, NA, NB>(tc, smem, A, B0, B1, C, row_index, index_div, N, K);
+    } else {
+        if constexpr (Cfg::NW == 4 && Cfg::TN == 8)
+            ring_tile_1w<Cfg, NA, NB>(tc, smem, A, B0, B1, C, row_index, index_div, N, K);
+        else
+            ring_tile<Cfg, NA, NB>(tc, smem, A, B0, B1, C, row_index, index_div, N, K);
+    }
 }
 
 }  // namespace gemm
