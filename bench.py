@@ -36,6 +36,8 @@ NOMINAL_SCLK_MHZ = 2400.0       # the shader clock the published peaks are quote
 # and it describes the library as it was when that file was written. Other runs report null.
 RECORDED_TRAFFIC = {
     # (workload, micro_tokens): (bytes per gate/up launch, profile file)
+    ("mixtral8x22b_prefill", None): (12.50e9, "profiles/expert_gemm_mixtral8x22b_prefill_hbm_traffic.md"),
+    ("mixtral8x22b_coalesce", 256): (3.244e9, "profiles/microbatched_mixtral8x22b_hbm_traffic.md"),
 }
 
 
@@ -137,8 +139,8 @@ def cpu_baseline(cfg, L, target_seconds=15.0):
     return out
 
 
-SUSTAINED_TFLOPS = 1330.0      # this library's gate/up kernel on large uniform expert groups
-SUSTAINED_GBS = 6100.0         # this library's weight streaming at 64 rows per expert
+SUSTAINED_TFLOPS = 1400.0      # this library's large tiles on uniform expert groups (measured; not a peak)
+SUSTAINED_GBS = 6100.0         # this library's weight streaming at 64 rows per expert (measured; not a peak)
 
 
 def planner_sweep(args, cfg, L, ctx, y, B, torch):
