@@ -651,6 +651,61 @@ __device__ __forceinline__ void ring_tile(const TileCoord& tc, unsigned char* sm
     store_tile<Cfg>(acc, tc, fp, wm, wn, C, N);
 }
 
+// Epilogue of the one-wavefront-per-SIMD tile: the outputs go through LDS so that global memory
+// sees whole cache lines. In the accumulator layout a lane holds four consecutive columns of one
+// row per fragment, so a direct store writes sixteen separate 32-byte pieces; 256 compute units
+// finishing their tiles together then queue at the L2 for thousands of cycles. Here a wavefront
+// writes the sixteen rows of fragment row i (8 bytes per lane and fragment) into a region of its
+// own in the now idle operand stages and reads them back 16 bytes per lane, one output row per
+// 16 lanes (8 with DUAL, whose rows are 64 columns): each store instruction then covers full
+// 128-byte lines. LDS serves a wavefront's requests in order, so the read after the write needs
+// no wait; the 16-byte chunks of a row are XOR-swizzled by the row so that both the writes
+// (16 rows at one column) and the reads (whole rows) spread over all banks.
+template <class Cfg>
+__device__ __forceinline__ void store_tile_via_lds(const f32x4 (&acc)[Cfg::TM][8], const TileCoord& tc,
+                                                   const FragPlan<Cfg>& fp, int wave, int lane,
+                                                   unsigned char* smem, uint16_t* __restrict__ C,
+                                                   int ldc) {
+    constexpr bool DUAL = Cfg::DUAL;
+    constexpr int TM = Cfg::TM, WN = Cfg::WN;
+    constexpr int ROWB = DUAL ? 128 : 256;           // bytes of one output row of this wavefront
+    constexpr int CP = ROWB / 16;                    // 16-byte chunks per row
+    constexpr int RSH = DUAL ? 1 : 0;                // log2 of the rows that share 256 bytes of LDS
+    constexpr int NJ = DUAL ? 4 : 8;                 // output fragments per fragment row
+    constexpr int RPI = 64 / CP;                     // rows per store instruction
+    static_assert(Cfg::TN == 8 && Cfg::NW * TM * 16 * ROWB <= Cfg::A_BYTES * 2 + Cfg::B_BYTES * 3, "fits the rings");
+    const int wm = wave / WN, wn = wave % WN;
+    unsigned char* stage = smem + wave * (TM * 16 * ROWB);
+    const uint32_t wswz = (fp.frag_row >> RSH) & (CP - 1);
+    unsigned char* wbase = stage + fp.frag_row * ROWB + (fp.frag_kg & 1) * 8;
+    const int rrow = lane / CP, rchunk = lane % CP;
+    uint16_t* cbase = C + static_cast<size_t>(tc.row0 + wm * Cfg::WTM) * ldc + tc.nt * Cfg::BN_OUT +
+                      wn * (ROWB / 2) + rchunk * 8;
+    const int rows_here = tc.rows - wm * Cfg::WTM;   // rows of this wavefront inside the tile
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+        for (int jj = 0; jj < NJ; ++jj) {
+            const int j = DUAL ? (jj & 1) + (jj >> 1) * 4 : jj;     // gate fragments; up = j + 2
+            bf16x4 o;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float v = DUAL ? silu(acc[i][j][r]) * acc[i][DUAL ? j + 2 : j][r] : acc[i][j][r];
+                o[r] = static_cast<__bf16>(v);                     // round to nearest even
+            }
+            const uint32_t chunk = (static_cast<uint32_t>(jj * 2 + (fp.frag_kg >> 1)) ^ wswz) * 16;
+            *reinterpret_cast<bf16x4*>(wbase + i * 16 * ROWB + chunk) = o;
+        }
+#pragma unroll
+        for (int q = 0; q < 16 / RPI; ++q) {
+            const int r = i * 16 + q * RPI + rrow;
+            const uint32_t chunk = (static_cast<uint32_t>(rchunk) ^ ((r >> RSH) & (CP - 1))) * 16;
+            const bf16x8 v = *reinterpret_cast<const bf16x8*>(stage + r * ROWB + chunk);
+            if (r < rows_here) *reinterpret_cast<bf16x8*>(cbase + static_cast<size_t>(r) * ldc) = v;
+        }
+    }
+}
+
 // f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>) in order
 template <int N, int I = 0, class F>
 __device__ __forceinline__ void static_for(F&& f) {
@@ -766,13 +821,17 @@ __device__ __forceinline__ void kstep_1w(f32x4 (&acc)[Cfg::TM][8], bf16x8 (&fa)[
                   "128 or 64 rows x 128 columns per wavefront");
     const uint32_t a_region = rs.a_region, b_region = rs.b_region;
     const unsigned char *pa_h1 = rs.pa_h1, *pb_h1 = rs.pb_h1, *pa_n0 = rs.pa_n0, *pb_n0 = rs.pb_n0;
-    // fragment read r of a half goes out behind MFMA r * NM / NR: B fragments first (every MFMA
-    // row needs all of them), then the A fragments in the order the MFMA rows use them
-    auto read_behind = [&](auto mtag, bf16x8 (&dfb)[8], bf16x8 (&dfa)[TM], const unsigned char* pbq,
-                           const unsigned char* paq) {
-        constexpr int m = decltype(mtag)::value;
-        constexpr int r = (m * NR + NM - 1) / NM;               // first read index with r * NM / NR >= m
-        if constexpr (r < NR && (r * NM) / NR == m) {
+    // fragment read r of a half goes out behind MFMA r * SPAN / NR: B fragments first (every MFMA
+    // row needs all of them), then the A fragments in the order the MFMA rows use them. The reads
+    // of the first half must all have returned at the barrier in the middle of the k-step, so
+    // they are spread over the first three quarters of it only; those of the second half have
+    // until their MFMA in the next k-step and are spread over the whole half.
+    constexpr int SPAN1 = (3 * NR <= NM) ? 3 * NR : 2 * NR;
+    auto read_behind = [&](auto mtag, auto spantag, bf16x8 (&dfb)[8], bf16x8 (&dfa)[TM],
+                           const unsigned char* pbq, const unsigned char* paq) {
+        constexpr int m = decltype(mtag)::value, SPAN = decltype(spantag)::value;
+        constexpr int r = (m * NR + SPAN - 1) / SPAN;           // first read index with r * SPAN / NR >= m
+        if constexpr (r < NR && (r * SPAN) / NR == m) {
             if constexpr (r < 8) dfb[r] = lds16(pbq + r * Cfg::TILE_STEP);
             else dfa[r - 8] = lds16(paq + (r - 8) * Cfg::TILE_STEP);
             MOE_FENCE();
@@ -785,7 +844,7 @@ __device__ __forceinline__ void kstep_1w(f32x4 (&acc)[Cfg::TM][8], bf16x8 (&fa)[
         const void* src = lp.b_src(wave, n < 8 ? n : 0);
         mma16_slot<m, NM / 8, 8>(fb[0][j], fa[0][i], acc[i][j], b_region, lp.b_voff, src);
         MOE_FENCE();
-        read_behind(mtag, fb[1], fa[1], pb_h1, pa_h1);
+        read_behind(mtag, std::integral_constant<int, SPAN1>{}, fb[1], fa[1], pb_h1, pa_h1);
         // the B pointers move on behind the last B load (MFMA 7 * NM / 8 + 3) while a later k-step exists
         constexpr int after_loads = 7 * (NM / 8) + 4;
         if constexpr (m == (after_loads < NM ? after_loads + 1 : NM - 1)) {
@@ -802,7 +861,7 @@ __device__ __forceinline__ void kstep_1w(f32x4 (&acc)[Cfg::TM][8], bf16x8 (&fa)[
         constexpr int m = decltype(mtag)::value, i = m >> 3, j = m & 7;
         mma16_slot<m, 8, LA>(fb[1][j], fa[1][i], acc[i][j], a_region, lp.a_voff, lp.a_ptr);
         MOE_FENCE();
-        read_behind(mtag, fb[0], fa[0], pb_n0, pa_n0);
+        read_behind(mtag, std::integral_constant<int, NM>{}, fb[0], fa[0], pb_n0, pa_n0);
         if constexpr (m == 1) { sb1 = rs.sb + BB; MOE_FENCE(); }
         if constexpr (m == 2) { sb1 = (sb1 == NB * BB) ? 0u : sb1; MOE_FENCE(); }        // stage of k-step kt+1
         if constexpr (m == 5) { sb2 = sb1 + BB; MOE_FENCE(); }
@@ -889,8 +948,9 @@ __device__ __forceinline__ void ring_tile_1w(const TileCoord& tc, unsigned char*
     for (int kt = 0; kt < KT; ++kt)
         kstep_1w<Cfg, NA, NB>(acc, fa, fb, rs, lp, wave, pa[0], pa[1], pb[0], pb[1], kt, KT);
     wait_vmcnt<0>();                                 // the refills of the last k-steps, never read
+    __builtin_amdgcn_s_barrier();                    // ... have all landed; nobody reads a stage any more
     mfma_drain();
-    store_tile<Cfg>(acc, tc, fp, wm, wn, C, N);
+    store_tile_via_lds<Cfg>(acc, tc, fp, wave, lane, smem, C, N);
 }
 
 // Tiles are enumerated at Cfg::BM rows. A tile that holds at most HalfCfg::BM = Cfg::BM / 2 rows
