@@ -89,8 +89,9 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def stage_model(cfg, T, calls_per_step):
-    """Algorithmic work of each stage for ONE layer call over T tokens (bytes or FLOPs)."""
+def stage_model(cfg, T, calls_per_step, yp_bytes=2):
+    """Algorithmic work of each stage for ONE layer call over T tokens (bytes or FLOPs);
+    yp_bytes: element size of the expert outputs between down projection and combine."""
     d, f, E, k = cfg.d_model, cfg.d_ff, cfg.E, cfg.k
     R = T * k
     return {
@@ -100,8 +101,8 @@ def stage_model(cfg, T, calls_per_step):
         "gateup": {"bound": "mfma", "flops": 4 * R * d * f,
                    "bytes": 4 * d * f * E * calls_per_step + R * 2 * d + R * 2 * f},
         "down": {"bound": "mfma", "flops": 2 * R * d * f,
-                 "bytes": 2 * d * f * E * calls_per_step + R * 2 * f + R * 2 * d},
-        "combine": {"bound": "hbm", "bytes": R * 2 * d + T * 2 * d},
+                 "bytes": 2 * d * f * E * calls_per_step + R * 2 * f + R * yp_bytes * d},
+        "combine": {"bound": "hbm", "bytes": R * yp_bytes * d + T * 2 * d},
     }
 
 
@@ -211,6 +212,9 @@ def main():
                          "next one, so that no operand of a step is still in a cache from the step "
                          "before (for presets whose weights fit the 256 MB Infinity Cache)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--fp32-expert-outputs", action="store_true",
+                    help="keep the expert outputs in fp32 between the down projection and the combine "
+                         "(moe_set_expert_output_fp32); the default, bf16, is what the headline is quoted on")
     ap.add_argument("--gemm-config", type=int, default=-1,
                     help="force the expert-GEMM tile configuration (0 large, 1 medium, 2 small, "
                          "3 tiny; +16 cached / +32 non-temporal weight loads); -1 = automatic")
@@ -288,6 +292,8 @@ def main():
     L = synth.make_layer(cfg, "cuda")
     ctx = B.MoeContext(T, cfg.d_model, cfg.d_ff, cfg.E, cfg.k)
     B.moe_set_gemm_config(ctx, args.gemm_config)
+    if args.fp32_expert_outputs:
+        B.moe_set_expert_output_fp32(ctx, True)
     if cfg.zipf_s is not None:
         idx = torch.empty((T, cfg.k), dtype=torch.int32, device="cuda")
         w = torch.empty((T, cfg.k), dtype=torch.float32, device="cuda")
@@ -404,7 +410,7 @@ def main():
 
     ms_per_step = elapsed / args.steps * 1e3
     chunks = (T + args.micro - 1) // args.micro if args.micro > 0 else 1
-    model = stage_model(cfg, T, chunks)
+    model = stage_model(cfg, T, chunks, 4 if args.fp32_expert_outputs else 2)
     stages = {}
     for name in B.STAGES:
         ms = stage_ms[name] / max(calls, 1)
@@ -443,7 +449,7 @@ def main():
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": cfg.name, "T": T, "d_model": cfg.d_model, "d_ff": cfg.d_ff, "E": cfg.E,
-                   "k": cfg.k, "micro_tokens": args.micro or None, "hip_graph": bool(args.graph),
+                   "k": cfg.k, "micro_tokens": args.micro or None, "hip_graph": bool(args.graph), "expert_outputs": "fp32" if args.fp32_expert_outputs else "bf16",
                    "rotated_buffers": args.rotate if args.rotate > 1 else None,
                    "rows_per_expert_last_call": counts.cpu().tolist()},
         "expert_gemm_TFLOP/s": gemm_tflops,

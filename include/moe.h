@@ -274,6 +274,20 @@ int moe_estimate_streamed_stage(const moe_shape* shape, const int32_t* rows, int
  * output element); only speed differs. Returns MOE_ERR_INVALID_ARG for other values. */
 int moe_set_gemm_config(moe_ctx* ctx, int config);
 
+/* Precision of the expert outputs Yp between the down projection and the combine inside
+ * moe_layer_forward, moe_layer_forward_microbatched and moe_layer_forward_streamed. The paper
+ * fixes 2-byte operands only (Table 1 row 3 counts bf16 weights and inputs); by default Yp is
+ * rounded to bf16 like the other intermediate, which is also what moe_expert_ffn and
+ * moe_combine exchange. enable != 0: the down projection stores its fp32 accumulators and the
+ * combine reads them, so an output element is rounded to bf16 once, after the gate-weighted
+ * sum, instead of twice; costs 2*T*k*d_model more bytes written and as many more read per
+ * call. Allocates a [T_max*k, d_model] fp32 buffer on the context's device, which must be the
+ * calling thread's current device (MOE_ERR_WORKSPACE if the allocation fails); enable == 0
+ * frees it again, the caller having drained the stream first. Routing, permutation and the
+ * accumulation order are unchanged; outputs of the two settings differ by that one rounding.
+ * Not a stream call: do not make it while a stream is being captured. */
+int moe_set_expert_output_fp32(moe_ctx* ctx, int enable);
+
 #ifdef __cplusplus
 }
 #endif

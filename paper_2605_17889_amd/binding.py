@@ -23,7 +23,7 @@ EXPORTS = (
     "moe_route_from_logits", "moe_permute", "moe_expert_ffn", "moe_combine", "moe_layer_forward",
     "moe_layer_forward_microbatched", "moe_last_routing", "moe_profile_begin", "moe_profile_end",
     "moe_set_gemm_config", "moe_estimate_expert_stage", "moe_layer_forward_streamed",
-    "moe_estimate_streamed_stage", "moe_permute_static",
+    "moe_estimate_streamed_stage", "moe_permute_static", "moe_set_expert_output_fp32",
 )
 
 
@@ -278,3 +278,8 @@ def moe_estimate_streamed_stage(d_model: int, d_ff: int, rows, n_moved: int, tfl
 
 def moe_set_gemm_config(ctx: MoeContext, config: int):
     _check(lib().moe_set_gemm_config(ctx._h, C.c_int(config)), "moe_set_gemm_config")
+
+
+def moe_set_expert_output_fp32(ctx: MoeContext, enable: bool):
+    _check(lib().moe_set_expert_output_fp32(ctx._h, C.c_int(1 if enable else 0)),
+           "moe_set_expert_output_fp32")

@@ -2,7 +2,8 @@
 // (the layer's defining sum over the selected experts). A per-token gather with a fixed slot
 // order in fp32, so the result is deterministic; no scatter, no atomics.
 //
-// HBM traffic per token: 2*d_model*k bytes read, 2*d_model bytes written.
+// HBM traffic per token: 2*d_model*k bytes read (4*d_model*k when the expert outputs were kept
+// in fp32), 2*d_model bytes written.
 #include "common.h"
 
 namespace moe {
@@ -10,8 +11,10 @@ namespace {
 
 constexpr int kMaxSlots = 64;
 
-// One block per token; each thread owns 8 consecutive columns (one 16-byte vector) per step.
-__global__ __launch_bounds__(256) void combine_kernel(const uint16_t* __restrict__ y_perm,
+// One block per token; each thread owns 8 consecutive columns per step (one 16-byte vector of
+// bf16 expert outputs, or two of fp32 ones with YF32).
+template <bool YF32>
+__global__ __launch_bounds__(256) void combine_kernel(const void* __restrict__ y_perm,
                                                       const int32_t* __restrict__ inv_perm,
                                                       const float* __restrict__ topk_w, int R,
                                                       int d, int k, uint16_t* __restrict__ y) {
@@ -31,12 +34,22 @@ __global__ __launch_bounds__(256) void combine_kernel(const uint16_t* __restrict
             const int p = row[s];
             if (static_cast<unsigned>(p) >= static_cast<unsigned>(R)) continue;  // dropped row
             const float g = gate[s];
-            const uint4 q = reinterpret_cast<const uint4*>(y_perm + static_cast<size_t>(p) * d)[c];
-            const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+            if constexpr (YF32) {
+                const float4* src =
+                    reinterpret_cast<const float4*>(static_cast<const float*>(y_perm) + static_cast<size_t>(p) * d) + 2 * c;
+                const float4 lo = src[0], hi = src[1];
+                const float w[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                acc[2 * v] = fmaf(g, __uint_as_float(w[v] << 16), acc[2 * v]);
-                acc[2 * v + 1] = fmaf(g, __uint_as_float(w[v] & 0xffff0000u), acc[2 * v + 1]);
+                for (int v = 0; v < 8; ++v) acc[v] = fmaf(g, w[v], acc[v]);
+            } else {
+                const uint4 q =
+                    reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(y_perm) + static_cast<size_t>(p) * d)[c];
+                const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    acc[2 * v] = fmaf(g, __uint_as_float(w[v] << 16), acc[2 * v]);
+                    acc[2 * v + 1] = fmaf(g, __uint_as_float(w[v] & 0xffff0000u), acc[2 * v + 1]);
+                }
             }
         }
         uint4 o;
@@ -50,11 +63,15 @@ __global__ __launch_bounds__(256) void combine_kernel(const uint16_t* __restrict
 
 }  // namespace
 
-int launch_combine(const moe_bf16* y_perm, const int32_t* inv_perm, const float* topk_w, int T,
+int launch_combine(const void* y_perm, bool y_f32, const int32_t* inv_perm, const float* topk_w, int T,
                    int d, int k, moe_bf16* y, hipStream_t s) {
     if (T == 0) return MOE_OK;
-    hipLaunchKernelGGL(combine_kernel, dim3(T), dim3(256), 0, s, y_perm, inv_perm, topk_w, T * k, d,
-                       k, y);
+    if (y_f32)
+        hipLaunchKernelGGL(combine_kernel<true>, dim3(T), dim3(256), 0, s, y_perm, inv_perm, topk_w,
+                           T * k, d, k, y);
+    else
+        hipLaunchKernelGGL(combine_kernel<false>, dim3(T), dim3(256), 0, s, y_perm, inv_perm, topk_w,
+                           T * k, d, k, y);
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
 

@@ -54,8 +54,8 @@ int launch_gateup(const GemmEnv& env, const moe_bf16* a, const int32_t* row_inde
                   const int32_t* offsets, int R, int R_hint, int d, int f, int E,
                   const moe_bf16* W1, const moe_bf16* W3, moe_bf16* H, hipStream_t s);
 int launch_down(const GemmEnv& env, const moe_bf16* H, const int32_t* offsets, int R, int R_hint,
-                int d, int f, int E, const moe_bf16* W2, moe_bf16* y_perm, hipStream_t s);
-int launch_combine(const moe_bf16* y_perm, const int32_t* inv_perm, const float* topk_w, int T,
+                int d, int f, int E, const moe_bf16* W2, void* y_perm, bool y_f32, hipStream_t s);
+int launch_combine(const void* y_perm, bool y_f32, const int32_t* inv_perm, const float* topk_w, int T,
                    int d, int k, moe_bf16* y, hipStream_t s);
 
 }  // namespace moe

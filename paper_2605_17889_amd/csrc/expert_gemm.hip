@@ -19,6 +19,8 @@ namespace moe {
 namespace {
 
 using gemm::Config;
+template <bool F32, class Cfg>
+using Out = std::conditional_t<F32, gemm::F32Out<Cfg>, Cfg>;
 
 
 // Compute units of a device (rounds of the pipelined kernel are that many tiles long).
@@ -178,43 +180,57 @@ int launch_gateup(const GemmEnv& env, const moe_bf16* a, const int32_t* row_inde
     }
 }
 
-int launch_down(const GemmEnv& env, const moe_bf16* H, const int32_t* offsets, int R, int R_hint,
-                int d, int f, int E, const moe_bf16* W2, moe_bf16* y_perm, hipStream_t s) {
+namespace {
+
+// F32: the same tilings with a float output matrix (gemm::F32Out).
+template <bool F32>
+int launch_down_as(const GemmEnv& env, const moe_bf16* H, const int32_t* offsets, int R, int R_hint,
+                   int d, int f, int E, const moe_bf16* W2, moe_bf16* y_perm, hipStream_t s) {
     if (R == 0) return MOE_OK;
     int config = pick_config(env, R_hint, E);
     if (config == 0 && f / 64 < 3) config = 1;     // the pipelined kernel needs three k-steps
     switch (config) {
         case 0:
             if (use_one_wave_per_simd(env, d, f))
-                return launch_ring<DownLarge1W, DownHalf1W, 2, 3>(env, H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
-            return launch_ring<DownLarge, DownMidWide, 2, 3>(env, H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
+                return launch_ring<Out<F32, DownLarge1W>, Out<F32, DownHalf1W>, 2, 3>(env, H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
+            return launch_ring<Out<F32, DownLarge>, Out<F32, DownMidWide>, 2, 3>(env, H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
         case 1:
             // HBM-bound: wide tiles stream more bytes per workgroup, but only if there are
             // enough of them to occupy the 256 compute units (about one m-tile per expert).
             if (static_cast<long long>(E) * (d / 256) >= 160 && d % 256 == 0) {
                 if (single_m_tile(env, R_hint, E, 128))
-                    return launch_grouped<DownMidWideS>(env, H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
-                return launch_grouped<DownMidWide>(env, H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
+                    return launch_grouped<Out<F32, DownMidWideS>>(env, H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
+                return launch_grouped<Out<F32, DownMidWide>>(env, H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
             }
             if (single_m_tile(env, R_hint, E, 128))
-                return launch_grouped<DownMidS>(env, H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
-            return launch_grouped<DownMid>(env, H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
+                return launch_grouped<Out<F32, DownMidS>>(env, H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
+            return launch_grouped<Out<F32, DownMid>>(env, H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
         case 3:
             // with fewer routed rows than experts only about R experts have a tile: narrower
             // tiles so that their weights still stream through most compute units
             if (static_cast<long long>(R_hint < E ? R_hint : E) * (d / 128) < 192 && single_m_tile(env, R_hint, E, 32))
-                return launch_grouped<DownTinyNarrowS>(env, H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
+                return launch_grouped<Out<F32, DownTinyNarrowS>>(env, H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
             if (d % 128 == 0) {
                 if (single_m_tile(env, R_hint, E, 32))
-                    return launch_grouped<DownTinyS>(env, H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
-                return launch_grouped<DownTiny>(env, H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
+                    return launch_grouped<Out<F32, DownTinyS>>(env, H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
+                return launch_grouped<Out<F32, DownTiny>>(env, H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
             }
             [[fallthrough]];
         default:
             if (single_m_tile(env, R_hint, E, 64))
-                return launch_grouped<DownSmallS>(env, H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
-            return launch_grouped<DownSmall>(env, H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
+                return launch_grouped<Out<F32, DownSmallS>>(env, H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
+            return launch_grouped<Out<F32, DownSmall>>(env, H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
     }
+}
+
+}  // namespace
+
+// y_perm is [R, d] bf16, or [R, d] fp32 when y_f32 is set.
+int launch_down(const GemmEnv& env, const moe_bf16* H, const int32_t* offsets, int R, int R_hint,
+                int d, int f, int E, const moe_bf16* W2, void* y_perm, bool y_f32, hipStream_t s) {
+    moe_bf16* out = static_cast<moe_bf16*>(y_perm);
+    return y_f32 ? launch_down_as<true>(env, H, offsets, R, R_hint, d, f, E, W2, out, s)
+                 : launch_down_as<false>(env, H, offsets, R, R_hint, d, f, E, W2, out, s);
 }
 
 }  // namespace moe

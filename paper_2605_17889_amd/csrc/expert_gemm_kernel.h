@@ -217,6 +217,19 @@ struct Config {
     static_assert(NSTAGE >= 2 && SMEM <= 160 * 1024, "LDS budget");
 };
 
+// The same tiling with fp32 outputs: C is then a float matrix. Used for the down projection
+// when the layer keeps the expert outputs in fp32 until the gate-weighted sum (one bf16
+// rounding fewer per output element); the accumulation is identical.
+template <class Cfg>
+struct F32Out : Cfg {
+    static constexpr bool OUT_F32 = true;
+    static_assert(!Cfg::DUAL, "the gate/up intermediate stays bf16");
+};
+template <class Cfg, class = void>
+struct out_is_f32 : std::false_type {};
+template <class Cfg>
+struct out_is_f32<Cfg, std::void_t<decltype(Cfg::OUT_F32)>> : std::bool_constant<Cfg::OUT_F32> {};
+
 // ---- pieces shared by the kernels ---------------------------------------------------------
 
 // MFMA 16x16x32 operand fragment: lane l supplies 8 consecutive k (k-group l >> 4) of operand
@@ -300,6 +313,12 @@ __device__ __forceinline__ void store_tile(const f32x4 (&acc)[Cfg::TM][Cfg::TN],
             if (DUAL && (j & 2)) continue;
             const int r0 = wn * Cfg::WTN + j * 16;                 // first B-tile row of tile j
             const int col = DUAL ? (r0 >> 6) * 32 + (r0 & 31) : r0;
+            if constexpr (out_is_f32<Cfg>::value) {
+                float* frow = reinterpret_cast<float*>(C) + static_cast<size_t>(tc.row0 + row) * ldc +
+                              tc.nt * Cfg::BN_OUT + 4 * fp.frag_kg;
+                *reinterpret_cast<f32x4*>(frow + col) = acc[i][j];
+                continue;
+            }
             bf16x4 o;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
@@ -655,53 +674,64 @@ __device__ __forceinline__ void ring_tile(const TileCoord& tc, unsigned char* sm
 // sees whole cache lines. In the accumulator layout a lane holds four consecutive columns of one
 // row per fragment, so a direct store writes sixteen separate 32-byte pieces; 256 compute units
 // finishing their tiles together then queue at the L2 for thousands of cycles. Here a wavefront
-// writes the sixteen rows of fragment row i (8 bytes per lane and fragment) into a region of its
-// own in the now idle operand stages and reads them back 16 bytes per lane, one output row per
-// 16 lanes (8 with DUAL, whose rows are 64 columns): each store instruction then covers full
-// 128-byte lines. LDS serves a wavefront's requests in order, so the read after the write needs
-// no wait; the 16-byte chunks of a row are XOR-swizzled by the row so that both the writes
-// (16 rows at one column) and the reads (whole rows) spread over all banks.
+// writes the sixteen rows of fragment row i into a small region of its own in the now idle
+// operand stages and reads them back 16 bytes per lane, whole rows at a time, so that each store
+// instruction covers full 128-byte lines; the region is reused for the next fragment row. LDS
+// serves a wavefront's requests in order, so neither the read after the write nor the next
+// write after the read needs a wait. The 16-byte chunks of a row are XOR-swizzled by the row so
+// that both the writes (16 rows at one column) and the reads (whole rows) spread over all banks.
 template <class Cfg>
 __device__ __forceinline__ void store_tile_via_lds(const f32x4 (&acc)[Cfg::TM][8], const TileCoord& tc,
                                                    const FragPlan<Cfg>& fp, int wave, int lane,
                                                    unsigned char* smem, uint16_t* __restrict__ C,
                                                    int ldc) {
-    constexpr bool DUAL = Cfg::DUAL;
+    constexpr bool DUAL = Cfg::DUAL, F32 = out_is_f32<Cfg>::value;
     constexpr int TM = Cfg::TM, WN = Cfg::WN;
-    constexpr int ROWB = DUAL ? 128 : 256;           // bytes of one output row of this wavefront
+    constexpr int COLS = DUAL ? 64 : 128;            // output columns of this wavefront
+    constexpr int ESZ = F32 ? 4 : 2;                 // bytes per output element
+    constexpr int ROWB = COLS * ESZ;                 // bytes of one output row of this wavefront
     constexpr int CP = ROWB / 16;                    // 16-byte chunks per row
-    constexpr int RSH = DUAL ? 1 : 0;                // log2 of the rows that share 256 bytes of LDS
+    constexpr int RSH = CP == 8 ? 1 : 0;             // log2 of the rows that share 256 bytes of LDS
+    constexpr int SWM = (CP < 16 ? CP : 16) - 1;     // the swizzle permutes chunks inside 256 bytes
     constexpr int NJ = DUAL ? 4 : 8;                 // output fragments per fragment row
     constexpr int RPI = 64 / CP;                     // rows per store instruction
-    static_assert(Cfg::TN == 8 && Cfg::NW * TM * 16 * ROWB <= Cfg::A_BYTES * 2 + Cfg::B_BYTES * 3, "fits the rings");
+    static_assert(Cfg::TN == 8 && Cfg::NW * 16 * ROWB <= 2 * Cfg::A_BYTES, "fits the A ring");
     const int wm = wave / WN, wn = wave % WN;
-    unsigned char* stage = smem + wave * (TM * 16 * ROWB);
-    const uint32_t wswz = (fp.frag_row >> RSH) & (CP - 1);
-    unsigned char* wbase = stage + fp.frag_row * ROWB + (fp.frag_kg & 1) * 8;
+    unsigned char* stage = smem + wave * (16 * ROWB);
+    const uint32_t wswz = (fp.frag_row >> RSH) & SWM;
+    unsigned char* wbase = stage + fp.frag_row * ROWB;
     const int rrow = lane / CP, rchunk = lane % CP;
-    uint16_t* cbase = C + static_cast<size_t>(tc.row0 + wm * Cfg::WTM) * ldc + tc.nt * Cfg::BN_OUT +
-                      wn * (ROWB / 2) + rchunk * 8;
+    const size_t row_bytes = static_cast<size_t>(ldc) * ESZ;
+    unsigned char* cbase = reinterpret_cast<unsigned char*>(C) +
+                           static_cast<size_t>(tc.row0 + wm * Cfg::WTM) * row_bytes +
+                           static_cast<size_t>(tc.nt * Cfg::BN_OUT + wn * COLS) * ESZ + rchunk * 16;
     const int rows_here = tc.rows - wm * Cfg::WTM;   // rows of this wavefront inside the tile
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
         for (int jj = 0; jj < NJ; ++jj) {
             const int j = DUAL ? (jj & 1) + (jj >> 1) * 4 : jj;     // gate fragments; up = j + 2
-            bf16x4 o;
+            if constexpr (F32) {
+                const uint32_t chunk = (static_cast<uint32_t>(jj * 4 + fp.frag_kg) ^ wswz) * 16;
+                *reinterpret_cast<f32x4*>(wbase + chunk) = acc[i][j];
+            } else {
+                bf16x4 o;
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const float v = DUAL ? silu(acc[i][j][r]) * acc[i][DUAL ? j + 2 : j][r] : acc[i][j][r];
-                o[r] = static_cast<__bf16>(v);                     // round to nearest even
+                for (int r = 0; r < 4; ++r) {
+                    const float v = DUAL ? silu(acc[i][j][r]) * acc[i][DUAL ? j + 2 : j][r] : acc[i][j][r];
+                    o[r] = static_cast<__bf16>(v);                 // round to nearest even
+                }
+                const uint32_t chunk = (static_cast<uint32_t>(jj * 2 + (fp.frag_kg >> 1)) ^ wswz) * 16;
+                *reinterpret_cast<bf16x4*>(wbase + chunk + (fp.frag_kg & 1) * 8) = o;
             }
-            const uint32_t chunk = (static_cast<uint32_t>(jj * 2 + (fp.frag_kg >> 1)) ^ wswz) * 16;
-            *reinterpret_cast<bf16x4*>(wbase + i * 16 * ROWB + chunk) = o;
         }
 #pragma unroll
         for (int q = 0; q < 16 / RPI; ++q) {
-            const int r = i * 16 + q * RPI + rrow;
-            const uint32_t chunk = (static_cast<uint32_t>(rchunk) ^ ((r >> RSH) & (CP - 1))) * 16;
-            const bf16x8 v = *reinterpret_cast<const bf16x8*>(stage + r * ROWB + chunk);
-            if (r < rows_here) *reinterpret_cast<bf16x8*>(cbase + static_cast<size_t>(r) * ldc) = v;
+            const int rl = q * RPI + rrow;                          // row inside the fragment row
+            const uint32_t chunk = (static_cast<uint32_t>(rchunk) ^ ((rl >> RSH) & SWM)) * 16;
+            const bf16x8 v = *reinterpret_cast<const bf16x8*>(stage + rl * ROWB + chunk);
+            const int r = i * 16 + rl;
+            if (r < rows_here) *reinterpret_cast<bf16x8*>(cbase + static_cast<size_t>(r) * row_bytes) = v;
         }
     }
 }

@@ -23,6 +23,7 @@ struct moe_ctx {
     moe_bf16* x_perm;    // [R_max, d]
     moe_bf16* H;         // [R_max, f]
     moe_bf16* y_perm;    // [R_max, d]
+    float* y_perm_f32;   // [R_max, d], allocated by moe_set_expert_output_fp32; null = keep bf16
     // profiling
     bool prof_armed;
     int prof_max_calls, prof_calls;
@@ -103,6 +104,11 @@ int run_stage(moe_ctx* c, int stage, int launches, hipStream_t s, Fn&& fn) {
     return rc;
 }
 
+// Where the layer calls keep the expert outputs Yp between the down projection and the combine.
+void* expert_out(moe_ctx* c) {
+    return c->y_perm_f32 ? static_cast<void*>(c->y_perm_f32) : static_cast<void*>(c->y_perm);
+}
+
 int forward_chunk(moe_ctx* c, const moe_bf16* x, const float* w_router, const float* bias,
                   const moe_bf16* W1, const moe_bf16* W3, const moe_bf16* W2, int T, moe_bf16* y,
                   hipStream_t s) {
@@ -135,11 +141,11 @@ int forward_chunk(moe_ctx* c, const moe_bf16* x, const float* w_router, const fl
     });
     if (rc != MOE_OK) return rc;
     rc = run_stage(c, MOE_STAGE_DOWN, 1, s, [&] {
-        return launch_down(c->gemm, c->H, c->offsets, R, R, d, f, E, W2, c->y_perm, s);
+        return launch_down(c->gemm, c->H, c->offsets, R, R, d, f, E, W2, expert_out(c), c->y_perm_f32 != nullptr, s);
     });
     if (rc != MOE_OK) return rc;
     return run_stage(c, MOE_STAGE_COMBINE, 1, s, [&] {
-        return launch_combine(c->y_perm, c->inv_perm, c->topk_w, T, d, k, y, s);
+        return launch_combine(expert_out(c), c->y_perm_f32 != nullptr, c->inv_perm, c->topk_w, T, d, k, y, s);
     });
 }
 
@@ -237,6 +243,7 @@ int moe_create(moe_ctx** out, const moe_shape* shape, int device_id) {
     c->x_perm = reinterpret_cast<moe_bf16*>(c->base + L.x_perm);
     c->H = reinterpret_cast<moe_bf16*>(c->base + L.H);
     c->y_perm = reinterpret_cast<moe_bf16*>(c->base + L.y_perm);
+    c->y_perm_f32 = nullptr;
     c->prof_armed = false;
     c->prof_max_calls = c->prof_calls = 0;
     for (auto& v : c->prof_launches) v = 0;
@@ -259,6 +266,7 @@ int moe_destroy(moe_ctx* c) {
         }
     }
     if (c->slot[0] && hipFree(c->slot[0]) != hipSuccess) rc = MOE_ERR_HIP;
+    if (c->y_perm_f32 && hipFree(c->y_perm_f32) != hipSuccess) rc = MOE_ERR_HIP;
     if (c->base && hipFree(c->base) != hipSuccess) rc = MOE_ERR_HIP;
     delete c;
     return rc;
@@ -313,7 +321,7 @@ int moe_expert_ffn(moe_ctx* c, const moe_bf16* x_perm, const int32_t* offsets, i
     const moe_shape& sh = c->shape;
     int rc = launch_gateup(c->gemm, x_perm, nullptr, 1, offsets, R, R, sh.d_model, sh.d_ff, sh.E, W1, W3, c->H, s);
     if (rc != MOE_OK) return rc;
-    return launch_down(c->gemm, c->H, offsets, R, R, sh.d_model, sh.d_ff, sh.E, W2, y_perm, s);
+    return launch_down(c->gemm, c->H, offsets, R, R, sh.d_model, sh.d_ff, sh.E, W2, y_perm, false, s);
 }
 
 int moe_combine(moe_ctx* c, const moe_bf16* y_perm, const int32_t* inv_perm, const float* topk_w,
@@ -322,7 +330,7 @@ int moe_combine(moe_ctx* c, const moe_bf16* y_perm, const int32_t* inv_perm, con
     if (!on_own_device(c)) return MOE_ERR_INVALID_ARG;
     if (T == 0) return MOE_OK;
     if (!y_perm || !inv_perm || !topk_w || !y) return MOE_ERR_INVALID_ARG;
-    return launch_combine(y_perm, inv_perm, topk_w, T, c->shape.d_model, c->shape.k, y,
+    return launch_combine(y_perm, false, inv_perm, topk_w, T, c->shape.d_model, c->shape.k, y,
                           static_cast<hipStream_t>(stream));
 }
 
@@ -412,7 +420,7 @@ int moe_layer_forward_streamed(moe_ctx* c, const moe_bf16* x, const float* w_rou
         });
         if (r != MOE_OK) return r;
         return run_stage(c, MOE_STAGE_DOWN, 1, s, [&] {
-            return launch_down(c->gemm, c->H, c->offsets + e0, R, hint, d, f, n, w2, c->y_perm, s);
+            return launch_down(c->gemm, c->H, c->offsets + e0, R, hint, d, f, n, w2, expert_out(c), c->y_perm_f32 != nullptr, s);
         });
     };
     if (E_res > 0 && (rc = ffn(0, E_res, W1, W3, W2)) != MOE_OK) return rc;
@@ -426,7 +434,7 @@ int moe_layer_forward_streamed(moe_ctx* c, const moe_bf16* x, const float* w_rou
         if (j + 2 < n_streamed && (rc = enqueue_copy(j + 2)) != MOE_OK) return rc;
     }
     return run_stage(c, MOE_STAGE_COMBINE, 1, s, [&] {
-        return launch_combine(c->y_perm, c->inv_perm, c->topk_w, T, d, k, y, s);
+        return launch_combine(expert_out(c), c->y_perm_f32 != nullptr, c->inv_perm, c->topk_w, T, d, k, y, s);
     });
 }
 
@@ -506,6 +514,29 @@ int moe_set_gemm_config(moe_ctx* c, int config) {
     c->gemm.large_tile_waves = large_waves;
     c->gemm.forced_config = config;
     c->gemm.stream_mode = stream_mode;
+    return MOE_OK;
+}
+
+int moe_set_expert_output_fp32(moe_ctx* c, int enable) {
+    if (!c) return MOE_ERR_INVALID_ARG;
+    if (!on_own_device(c)) return MOE_ERR_INVALID_ARG;
+    if (enable) {
+        if (c->y_perm_f32) return MOE_OK;
+        const size_t bytes = static_cast<size_t>(c->shape.T_max) * c->shape.k * c->shape.d_model * sizeof(float);
+        void* p = nullptr;
+        if (hipMalloc(&p, bytes > 0 ? bytes : 256) != hipSuccess) {
+            (void)hipGetLastError();
+            return MOE_ERR_WORKSPACE;
+        }
+        c->y_perm_f32 = static_cast<float*>(p);
+        return MOE_OK;
+    }
+    if (c->y_perm_f32) {
+        // the caller has drained the stream (as for moe_destroy)
+        const hipError_t err = hipFree(c->y_perm_f32);
+        c->y_perm_f32 = nullptr;
+        if (err != hipSuccess) return MOE_ERR_HIP;
+    }
     return MOE_OK;
 }
 

@@ -519,7 +519,11 @@ def test_layer_mixtral8x22b_prefill(experts_8x22b):
     say(f"    rows per expert {routing['counts'].tolist()}")
     tokens = sample_tokens(cfg, o_ref, p_ref, 64, 2)
     want, _, _ = ref.layer_tokens(Hh["x"], Hh["w_router"], None, Hh["W1"], Hh["W3"], Hh["W2"], cfg.k, tokens)
-    assert_close_ffn(bits(y)[tokens], want, f"8x22B prefill ({tokens.size} tokens)")
+    rel16, _ = assert_close_ffn(bits(y)[tokens], want, f"8x22B prefill ({tokens.size} tokens)")
+    B.moe_set_expert_output_fp32(ctx, True)
+    y32, _ = run_layer(cfg, L, ctx=ctx)
+    rel32, _ = assert_close_ffn(bits(y32)[tokens], want, "8x22B prefill, fp32 expert outputs")
+    assert rel32 < rel16, (rel32, rel16)
     ctx.close()
 
 
@@ -747,6 +751,54 @@ def test_layer_other_expert_shapes(T, d, f, E, k, use_bias):
     assert_close_ffn(bits(y), want, f"E={E} k={k}")
     ym, _ = run_layer(cfg, L, micro=37, ctx=ctx)
     assert torch.equal(ym.view(torch.int16), y.view(torch.int16)), "micro-batched output differs"
+    ctx.close()
+
+
+# ---------------------------------------------- expert outputs kept in fp32 until the combine
+@pytest.mark.parametrize("T,d,f,E,k", [
+    (256, 512, 1024, 8, 2),        # the tiny preset's shape: one short row tile per expert
+    (1500, 1024, 2048, 4, 2),      # ~750 rows per expert: full, partial and half-height 256-row tiles
+    (300, 2048, 768, 128, 8),      # many small experts
+])
+def test_layer_fp32_expert_outputs(T, d, f, E, k):
+    """moe_set_expert_output_fp32: the down projection stores fp32 and the combine reads it, so
+    an output element sees one bf16 rounding fewer. Checked against the oracle on every token
+    (closer than the default path), and for the invariances the default path has: micro-batched
+    == coalesced, every tile configuration gives the same bits, streamed experts give the same
+    bits, and switching the option off restores the default bits."""
+    say(f"layer T={T} d={d} f={f} E={E} k={k}: fp32 expert outputs")
+    cfg = synth.LayerConfig("custom", T, d, f, E, k, seed=4100 + E)
+    L = synth.make_layer(cfg, "cuda")
+    Hh = host_layer(L)
+    want, _, _ = ref.layer_tokens(Hh["x"], Hh["w_router"], None, Hh["W1"], Hh["W3"], Hh["W2"], k)
+    y16, ctx = run_layer(cfg, L)
+    rel16, _ = assert_close_ffn(bits(y16), want, "bf16 expert outputs")
+    B.moe_set_expert_output_fp32(ctx, True)
+    B.moe_set_expert_output_fp32(ctx, True)          # idempotent
+    y32, _ = run_layer(cfg, L, ctx=ctx)
+    rel32, _ = assert_close_ffn(bits(y32), want, "fp32 expert outputs")
+    assert rel32 < rel16, (rel32, rel16)
+    for m in (37, 256):
+        ym, _ = run_layer(cfg, L, micro=m, ctx=ctx)
+        assert torch.equal(ym.view(torch.int16), y32.view(torch.int16)), f"micro m={m} differs"
+    if E <= 16:
+        # a 37-token micro-batch runs the small tiles, the coalesced call of the middle shape the
+        # large ones; force each configuration as well
+        for config in ALL_TILE_CONFIGS + [0 + 512 + 128]:
+            B.moe_set_gemm_config(ctx, config)
+            yc, _ = run_layer(cfg, L, ctx=ctx)
+            assert torch.equal(yc.view(torch.int16), y32.view(torch.int16)), f"config {config} differs"
+        B.moe_set_gemm_config(ctx, -1)
+    n = min(3, E)
+    host = [pinned_tail(L[name], n) for name in ("W1", "W3", "W2")]
+    dev_w = [L[name][:E - n].contiguous() for name in ("W1", "W3", "W2")]
+    ys = torch.full((T, d), float("nan"), dtype=torch.bfloat16, device="cuda")
+    B.moe_layer_forward_streamed(ctx, L["x"], L["w_router"], L["bias"], *dev_w, *host, n, T, ys)
+    torch.cuda.synchronize()
+    assert torch.equal(ys.view(torch.int16), y32.view(torch.int16)), "streamed differs"
+    B.moe_set_expert_output_fp32(ctx, False)
+    yb, _ = run_layer(cfg, L, ctx=ctx)
+    assert torch.equal(yb.view(torch.int16), y16.view(torch.int16)), "default bits not restored"
     ctx.close()
 
 
