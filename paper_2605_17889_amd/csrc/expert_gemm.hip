@@ -109,6 +109,7 @@ int pick_config(const GemmEnv& env, int R, int E) {
 // four-wavefront form addresses a weight row by a 32-bit byte offset from the expert's matrix.
 bool use_one_wave_per_simd(const GemmEnv& env, int N, int K) {
     if (static_cast<unsigned long long>(N) * K * 2ull >= (1ull << 32)) return false;
+    if (K % 128 != 0) return false;       // its k-loop takes two 64-wide steps per trip
     if (env.large_tile_waves != 0) return env.large_tile_waves == 4;
     return true;     // faster at every shape measured (reductions of 768 to 16384)
 }

@@ -975,8 +975,12 @@ __device__ __forceinline__ void ring_tile_1w(const TileCoord& tc, unsigned char*
     // k-step 0: stages 0; its B loads refill the stage "before" it, NB-1, which is still empty
     RingState1W rs{pa[1], pb[1], pa[0] + AB, pb[0] + BB, lp.a_lds,
                    R::A_RING + (NB - 1) * BB + lp.b_lds, 0u, 0u};
-    for (int kt = 0; kt < KT; ++kt)
+    // two k-steps per trip (K is a multiple of 128 for every supported shape): the loop's own
+    // compare-and-branch then falls between MFMAs half as often
+    for (int kt = 0; kt < KT; kt += 2) {
         kstep_1w<Cfg, NA, NB>(acc, fa, fb, rs, lp, wave, pa[0], pa[1], pb[0], pb[1], kt, KT);
+        kstep_1w<Cfg, NA, NB>(acc, fa, fb, rs, lp, wave, pa[0], pa[1], pb[0], pb[1], kt + 1, KT);
+    }
     wait_vmcnt<0>();                                 // the refills of the last k-steps, never read
     __builtin_amdgcn_s_barrier();                    // ... have all landed; nobody reads a stage any more
     mfma_drain();
