@@ -62,11 +62,17 @@ struct TileCoord {
 // than half full, each of its tiles is handed to two workgroups as an upper and a lower half
 // of BM/2 rows, so that the round ends after a half-height tile instead of a full one. The
 // halves are the highest slots of every XCD's range, hence the last workgroups dispatched.
+//
+// The tile is named by (xcd, slot): slot-th entry of XCD xcd's range. The one-launch-per-tile
+// kernels take both from the workgroup index; the persistent kernel draws slots from a counter.
+// Result: expert >= 0: a tile; kNoTile: the range is exhausted (every later slot is too);
+// kEmptySlot: this slot holds nothing (the lower half of a tile that has none), later ones may.
+constexpr int kNoTile = -1, kEmptySlot = -2;
 template <int BM>
-__device__ __forceinline__ TileCoord locate_tile(const int32_t* __restrict__ offsets, int E,
-                                                 int NT, int split_cus = 0) {
+__device__ __forceinline__ TileCoord locate_tile_at(const int32_t* __restrict__ offsets, int E,
+                                                    int NT, int split_cus, int xcd, int slot) {
     constexpr int EW = kMaxExperts / kWave;
-    TileCoord tc{-1, 0, 0, 0, 0, 1};
+    TileCoord tc{kNoTile, 0, 0, 0, 0, 1};
     const int lane = threadIdx.x & (kWave - 1);
     int rows[EW], first[EW], tiles[EW], incl[EW];     // per expert of this lane; incl: prefix sum
     int carry = 0;
@@ -91,8 +97,6 @@ __device__ __forceinline__ TileCoord locate_tile(const int32_t* __restrict__ off
     }
     const int total = __builtin_amdgcn_readfirstlane(carry);
     const int per = (total + kXcds - 1) / kXcds;
-    const int xcd = blockIdx.x % kXcds;
-    const int slot = blockIdx.x / kXcds;
     const int len = max(0, min(per, total - xcd * per));   // tiles in this XCD's range
     int halved = 0;                                        // of those, the last `halved` are split
     if (split_cus > 0) {
@@ -140,7 +144,10 @@ __device__ __forceinline__ TileCoord locate_tile(const int32_t* __restrict__ off
         int row0 = row_e + mi * BM, nrows = min(BM, m_e - mi * BM);
         if (half >= 0) {
             const int h0 = half * (BM / 2);
-            if (nrows <= h0) return tc;                // the tile has no lower half
+            if (nrows <= h0) {                         // the tile has no lower half
+                tc.expert = kEmptySlot;
+                return tc;
+            }
             row0 += h0;
             nrows = min(BM / 2, nrows - h0);
         }
@@ -153,6 +160,12 @@ __device__ __forceinline__ TileCoord locate_tile(const int32_t* __restrict__ off
         return tc;
     }
     return tc;
+}
+
+template <int BM>
+__device__ __forceinline__ TileCoord locate_tile(const int32_t* __restrict__ offsets, int E,
+                                                 int NT, int split_cus = 0) {
+    return locate_tile_at<BM>(offsets, E, NT, split_cus, blockIdx.x % kXcds, blockIdx.x / kXcds);
 }
 
 // LDS tile layout: rows of BK bf16 in 16-byte chunks; logical chunk c of row r is stored at
@@ -758,13 +771,18 @@ __device__ __forceinline__ void static_for(F&& f) {
 // The A loads of k-step kt+NA go out in the second half of k-step kt, the B loads of k-step
 // kt+NB in the first half of k-step kt+1, so the texture-address unit sees one load per SIMD
 // every 128 cycles throughout instead of all sixteen within one half.
-template <class Cfg>
-struct LoadPlan1W {
-    static constexpr int LA = Cfg::NIA / Cfg::NW, LB = Cfg::NIB / Cfg::NW;
+// Storage of a wavefront's load plan, the same for the full and the half-height tile (which
+// uses the first four A entries), so that one tile's code can prepare the next tile's plan.
+struct LoadPlanData1W {
     const uint16_t* a_ptr;          // A origin + current k offset of the A loads
     const uint16_t* b_ptr[2];       // expert's W (and W3 with DUAL) + current k offset of the B loads
-    uint32_t a_voff[LA], b_voff[LB];
+    uint32_t a_voff[8], b_voff[8];
     uint32_t a_lds, b_lds;          // this wavefront's first load inside an A / B stage
+};
+template <class Cfg>
+struct LoadPlan1W : LoadPlanData1W {
+    static constexpr int LA = Cfg::NIA / Cfg::NW, LB = Cfg::NIB / Cfg::NW;
+    static_assert(LA <= 8 && LB == 8, "plan storage");
     __device__ __forceinline__ void init(const TileCoord& tc, int wave, int lane, const uint16_t* A,
                                          const uint16_t* B0, const uint16_t* B1,
                                          const int32_t* row_index, int index_div, int N, int K) {
@@ -915,40 +933,19 @@ __device__ __forceinline__ void kstep_1w(f32x4 (&acc)[Cfg::TM][8], bf16x8 (&fa)[
     rs = nx;
 }
 
+// The first loads of a tile: A stages 0..NA-1 and B stages 0..NB-2, in the order the k-loop
+// issues them; the first half of k-step 0 adds B stage NB-1 like any other k-step.
 template <class Cfg, int NA, int NB>
-__device__ __forceinline__ void ring_tile_1w(const TileCoord& tc, unsigned char* smem,
-                                             const uint16_t* __restrict__ A,
-                                             const uint16_t* __restrict__ B0,
-                                             const uint16_t* __restrict__ B1, uint16_t* __restrict__ C,
-                                             const int32_t* __restrict__ row_index, int index_div,
-                                             int N, int K) {
+__device__ __forceinline__ void prologue_1w(const TileCoord& tc, LoadPlan1W<Cfg>& lp, int wave, int lane,
+                                            const uint16_t* __restrict__ A,
+                                            const uint16_t* __restrict__ B0,
+                                            const uint16_t* __restrict__ B1,
+                                            const int32_t* __restrict__ row_index, int index_div,
+                                            int N, int K) {
     using R = RingCfg<Cfg, NA, NB>;
-    constexpr int BK = Cfg::BK, WN = Cfg::WN, TM = Cfg::TM, TN = Cfg::TN;
-    constexpr int LA = R::LA, LB = R::LB, AB = Cfg::A_BYTES, BB = Cfg::B_BYTES;
-    static_assert(BK == 64 && NA == 2 && NB == 3 && TN == 8, "rings of 2 + 3 stages of 64 k");
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave / WN, wn = wave % WN;
-
-    LoadPlan1W<Cfg> lp;
+    constexpr int BK = Cfg::BK, LA = R::LA, LB = R::LB, AB = Cfg::A_BYTES, BB = Cfg::B_BYTES;
+    static_assert(NB - 1 == NA, "prologue order");
     lp.init(tc, wave, lane, A, B0, B1, row_index, index_div, N, K);
-    FragPlan<Cfg> fp;
-    fp.init(lane, wm, wn);
-    const unsigned char* pa[2] = {smem + fp.a_off[0], smem + fp.a_off[1]};
-    const unsigned char* pb[2] = {smem + R::A_RING + (fp.b_off[0] - AB), smem + R::A_RING + (fp.b_off[1] - AB)};
-
-    f32x4 acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
-    mfma_drain();                                    // accumulator writes settle before MFMAs
-
-    const int KT = K / BK;                           // >= NB (checked by the launcher)
-    // prologue: A stages 0..NA-1 and B stages 0..NB-2, in the order the k-loop issues them; the
-    // first half of k-step 0 adds B stage NB-1 like any other k-step
 #pragma unroll
     for (int s = 0; s < NA; ++s) {
 #pragma unroll
@@ -962,7 +959,37 @@ __device__ __forceinline__ void ring_tile_1w(const TileCoord& tc, unsigned char*
             if (Cfg::DUAL) lp.b_ptr[1] += BK;
         }
     }
-    static_assert(NB - 1 == NA, "prologue order");
+}
+
+// From the landing of k-step 0 to the last MFMA: on return every load has landed, every
+// wavefront has passed the closing barrier (nobody reads a stage any more) and the accumulators
+// hold the tile.
+template <class Cfg, int NA, int NB>
+__device__ __forceinline__ void mainloop_1w(f32x4 (&acc)[Cfg::TM][8], LoadPlan1W<Cfg>& lp,
+                                            const FragPlan<Cfg>& fp, unsigned char* smem, int wave,
+                                            int K) {
+    using R = RingCfg<Cfg, NA, NB>;
+    constexpr int BK = Cfg::BK, TM = Cfg::TM, TN = Cfg::TN;
+    constexpr int LA = R::LA, LB = R::LB, AB = Cfg::A_BYTES, BB = Cfg::B_BYTES;
+    static_assert(BK == 64 && NA == 2 && NB == 3 && TN == 8, "rings of 2 + 3 stages of 64 k");
+    const unsigned char* pa[2] = {smem + fp.a_off[0], smem + fp.a_off[1]};
+    const unsigned char* pb[2] = {smem + R::A_RING + (fp.b_off[0] - AB), smem + R::A_RING + (fp.b_off[1] - AB)};
+    // The accumulators start as the result of an MFMA, 0 * 0 + 0, not as ordinary register
+    // writes: the compiler may sink those to just in front of the k-loop, and it cannot know
+    // that the inline assembly there is an MFMA that needs wait states after them (it did
+    // exactly that once the zeroing stood after the first loads, and a few fragments came out
+    // wrong). MFMA after MFMA on the same registers needs nothing.
+    {
+        const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+        asm volatile("s_nop 4" :: "v"(zero));
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %1, 0" : "=a"(acc[i][j]) : "v"(zero));
+    }
+
+    const int KT = K / BK;                           // >= NB (checked by the launcher)
     wait_vmcnt<(NA - 1) * (LA + LB)>();              // k-step 0 landed
     __builtin_amdgcn_s_barrier();
     bf16x8 fa[2][TM], fb[2][TN];
@@ -983,6 +1010,24 @@ __device__ __forceinline__ void ring_tile_1w(const TileCoord& tc, unsigned char*
     }
     wait_vmcnt<0>();                                 // the refills of the last k-steps, never read
     __builtin_amdgcn_s_barrier();                    // ... have all landed; nobody reads a stage any more
+}
+
+template <class Cfg, int NA, int NB>
+__device__ __forceinline__ void ring_tile_1w(const TileCoord& tc, unsigned char* smem,
+                                             const uint16_t* __restrict__ A,
+                                             const uint16_t* __restrict__ B0,
+                                             const uint16_t* __restrict__ B1, uint16_t* __restrict__ C,
+                                             const int32_t* __restrict__ row_index, int index_div,
+                                             int N, int K) {
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    LoadPlan1W<Cfg> lp;
+    prologue_1w<Cfg, NA, NB>(tc, lp, wave, lane, A, B0, B1, row_index, index_div, N, K);
+    FragPlan<Cfg> fp;
+    fp.init(lane, wave / Cfg::WN, wave % Cfg::WN);
+    f32x4 acc[Cfg::TM][Cfg::TN];
+    mainloop_1w<Cfg, NA, NB>(acc, lp, fp, smem, wave, K);
     mfma_drain();
     store_tile_via_lds<Cfg>(acc, tc, fp, wave, lane, smem, C, N);
 }
