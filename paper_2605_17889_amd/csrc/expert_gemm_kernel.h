@@ -63,10 +63,9 @@ struct TileCoord {
 // of BM/2 rows, so that the round ends after a half-height tile instead of a full one. The
 // halves are the highest slots of every XCD's range, hence the last workgroups dispatched.
 //
-// The tile is named by (xcd, slot): slot-th entry of XCD xcd's range. The one-launch-per-tile
-// kernels take both from the workgroup index; the persistent kernel draws slots from a counter.
-// Result: expert >= 0: a tile; kNoTile: the range is exhausted (every later slot is too);
-// kEmptySlot: this slot holds nothing (the lower half of a tile that has none), later ones may.
+// The tile is named by (xcd, slot): slot-th entry of XCD xcd's range; the kernels take both from
+// the workgroup index. Result: expert >= 0: a tile; kNoTile: the range is exhausted (every later
+// slot is too); kEmptySlot: this slot holds nothing (the lower half of a tile that has none).
 constexpr int kNoTile = -1, kEmptySlot = -2;
 template <int BM>
 __device__ __forceinline__ TileCoord locate_tile_at(const int32_t* __restrict__ offsets, int E,
@@ -746,6 +745,7 @@ __device__ __forceinline__ void store_tile_via_lds(const f32x4 (&acc)[Cfg::TM][8
             const int r = i * 16 + rl;
             if (r < rows_here) *reinterpret_cast<bf16x8*>(cbase + static_cast<size_t>(r) * row_bytes) = v;
         }
+        MOE_FENCE();                                 // one fragment row's registers at a time
     }
 }
 
@@ -1010,6 +1010,7 @@ __device__ __forceinline__ void mainloop_1w(f32x4 (&acc)[Cfg::TM][8], LoadPlan1W
     }
     wait_vmcnt<0>();                                 // the refills of the last k-steps, never read
     __builtin_amdgcn_s_barrier();                    // ... have all landed; nobody reads a stage any more
+    mfma_drain();                                    // before anything else touches the accumulators
 }
 
 template <class Cfg, int NA, int NB>
@@ -1028,7 +1029,6 @@ __device__ __forceinline__ void ring_tile_1w(const TileCoord& tc, unsigned char*
     fp.init(lane, wave / Cfg::WN, wave % Cfg::WN);
     f32x4 acc[Cfg::TM][Cfg::TN];
     mainloop_1w<Cfg, NA, NB>(acc, lp, fp, smem, wave, K);
-    mfma_drain();
     store_tile_via_lds<Cfg>(acc, tc, fp, wave, lane, smem, C, N);
 }
 
