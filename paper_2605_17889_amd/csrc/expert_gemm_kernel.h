@@ -771,18 +771,13 @@ __device__ __forceinline__ void static_for(F&& f) {
 // The A loads of k-step kt+NA go out in the second half of k-step kt, the B loads of k-step
 // kt+NB in the first half of k-step kt+1, so the texture-address unit sees one load per SIMD
 // every 128 cycles throughout instead of all sixteen within one half.
-// Storage of a wavefront's load plan, the same for the full and the half-height tile (which
-// uses the first four A entries), so that one tile's code can prepare the next tile's plan.
-struct LoadPlanData1W {
+template <class Cfg>
+struct LoadPlan1W {
+    static constexpr int LA = Cfg::NIA / Cfg::NW, LB = Cfg::NIB / Cfg::NW;
     const uint16_t* a_ptr;          // A origin + current k offset of the A loads
     const uint16_t* b_ptr[2];       // expert's W (and W3 with DUAL) + current k offset of the B loads
-    uint32_t a_voff[8], b_voff[8];
+    uint32_t a_voff[LA], b_voff[LB];
     uint32_t a_lds, b_lds;          // this wavefront's first load inside an A / B stage
-};
-template <class Cfg>
-struct LoadPlan1W : LoadPlanData1W {
-    static constexpr int LA = Cfg::NIA / Cfg::NW, LB = Cfg::NIB / Cfg::NW;
-    static_assert(LA <= 8 && LB == 8, "plan storage");
     __device__ __forceinline__ void init(const TileCoord& tc, int wave, int lane, const uint16_t* A,
                                          const uint16_t* B0, const uint16_t* B1,
                                          const int32_t* row_index, int index_div, int N, int K) {
