@@ -227,7 +227,9 @@ def main():
                          "gate/up and down shapes of the workload with uniform expert groups "
                          "folded into one matrix, with the same clock and power sampling: what a "
                          "tuned dense kernel reaches on this machine at this shape (a yardstick "
-                         "for the expert GEMMs, not part of the path)")
+                         "for the expert GEMMs, not part of the path), followed by this library's "
+                         "two grouped GEMMs on uniform expert groups of the same size "
+                         "(moe_expert_ffn)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy 10 times (to scale rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE counters against a kernel of known traffic)")
@@ -281,7 +283,38 @@ def main():
                          "frac_of_bf16_peak": flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
                          "sclk_MHz_median": mhz, "board_power_W_median": watts}
             del a, w
-        print(json.dumps({"vendor_gemm_yardstick": out}), flush=True)
+        # the same two contractions by this library's kernels on uniform expert groups of the
+        # same total size (moe_expert_ffn: no routing, no gather), to separate what the kernels
+        # do from what ragged routed groups cost
+        E, T = cfg.E, (args.tokens or cfg.T)
+        L = synth.make_layer(cfg, "cuda")
+        ctx = B.MoeContext(T, d, f, E, cfg.k)
+        B.moe_set_gemm_config(ctx, args.gemm_config)
+        per = R // E
+        offsets = (torch.arange(E + 1, dtype=torch.int32) * per).cuda()
+        xp = mk(per * E, d, 1.0)
+        yp = torch.empty((per * E, d), dtype=torch.bfloat16, device="cuda")
+        for _ in range(3):
+            B.moe_expert_ffn(ctx, xp, offsets, per * E, L["W1"], L["W3"], L["W2"], yp)
+        torch.cuda.synchronize()
+        n = 60
+        clock = ClockSampler()
+        clock.start()
+        B.moe_profile_begin(ctx, n)
+        for _ in range(n):
+            B.moe_expert_ffn(ctx, xp, offsets, per * E, L["W1"], L["W3"], L["W2"], yp)
+        torch.cuda.synchronize()
+        stage_ms, _, calls = B.moe_profile_end(ctx)
+        mhz, watts = clock.stop()
+        ours = {"rows_per_expert": per, "experts": E, "calls": calls,
+                "sclk_MHz_median": mhz, "board_power_W_median": watts}
+        for name, fl in (("gateup", 4.0 * per * E * d * f), ("down", 2.0 * per * E * d * f)):
+            ms = stage_ms[name] / max(calls, 1)
+            ours[name] = {"ms": ms, "TFLOP/s": fl / (ms * 1e-3) / 1e12,
+                          "frac_of_bf16_peak": fl / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
+        ctx.close()
+        print(json.dumps({"vendor_gemm_yardstick": out,
+                          "this_library_uniform_groups": ours}), flush=True)
         return
     cfg = synth.PRESETS[args.workload]
     if args.tokens > 0:

@@ -200,8 +200,9 @@ int moe_last_routing(moe_ctx* ctx, int32_t T, int32_t* topk_idx, float* topk_w, 
                      int32_t* offsets, int32_t* perm, int32_t* inv_perm, void* stream);
 
 /* Per-stage device timing for measurement. moe_profile_begin() arms up to `max_calls`
- * subsequent moe_layer_forward / moe_layer_forward_microbatched calls: each records HIP
- * events on the caller's stream between stages. moe_profile_end() waits for those events and
+ * subsequent moe_layer_forward / moe_layer_forward_microbatched / moe_layer_forward_streamed /
+ * moe_expert_ffn calls: each records HIP events on the caller's stream between stages (the
+ * two GEMM stages for moe_expert_ffn). moe_profile_end() waits for those events and
  * writes, per stage, the total milliseconds (stage_ms[MOE_NUM_STAGES], host), the number of
  * kernel launches (stage_launches[MOE_NUM_STAGES], host) and the number of layer calls
  * covered (*calls), then disarms. Costs two event records per stage while armed. */

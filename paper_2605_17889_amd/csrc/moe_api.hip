@@ -319,9 +319,14 @@ int moe_expert_ffn(moe_ctx* c, const moe_bf16* x_perm, const int32_t* offsets, i
     if (!x_perm || !offsets || !W1 || !W3 || !W2 || !y_perm) return MOE_ERR_INVALID_ARG;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const moe_shape& sh = c->shape;
-    int rc = launch_gateup(c->gemm, x_perm, nullptr, 1, offsets, R, R, sh.d_model, sh.d_ff, sh.E, W1, W3, c->H, s);
+    if (c->prof_armed) ++c->prof_calls;
+    int rc = run_stage(c, MOE_STAGE_GATEUP, 1, s, [&] {
+        return launch_gateup(c->gemm, x_perm, nullptr, 1, offsets, R, R, sh.d_model, sh.d_ff, sh.E, W1, W3, c->H, s);
+    });
     if (rc != MOE_OK) return rc;
-    return launch_down(c->gemm, c->H, offsets, R, R, sh.d_model, sh.d_ff, sh.E, W2, y_perm, false, s);
+    return run_stage(c, MOE_STAGE_DOWN, 1, s, [&] {
+        return launch_down(c->gemm, c->H, offsets, R, R, sh.d_model, sh.d_ff, sh.E, W2, y_perm, false, s);
+    });
 }
 
 int moe_combine(moe_ctx* c, const moe_bf16* y_perm, const int32_t* inv_perm, const float* topk_w,
