@@ -802,6 +802,41 @@ def test_layer_fp32_expert_outputs(T, d, f, E, k):
     ctx.close()
 
 
+def test_profile_stage_times_of_layer_and_expert_ffn():
+    """moe_profile_begin / moe_profile_end: a layer call records all of its stages, a standalone
+    moe_expert_ffn call its two GEMM stages; launches and calls are counted; the outputs are the
+    bits of an unprofiled call."""
+    cfg = synth.PRESETS["tiny"]
+    say("stage profiling: layer call and moe_expert_ffn")
+    L = synth.make_layer(cfg, "cuda")
+    y_plain, ctx = run_layer(cfg, L)
+    B.moe_profile_begin(ctx, 3)
+    for _ in range(3):
+        y_prof, _ = run_layer(cfg, L, ctx=ctx)
+    stage_ms, launches, calls = B.moe_profile_end(ctx)
+    assert calls == 3
+    assert torch.equal(y_prof.view(torch.int16), y_plain.view(torch.int16))
+    for name in ("route", "permute", "gateup", "down", "combine"):
+        assert stage_ms[name] > 0 and launches[name] >= 3, (name, stage_ms, launches)
+    assert stage_ms["gather"] == 0 and launches["gather"] == 0     # fused into the gate/up loads
+    routing = fetch_routing(ctx, cfg.T)
+    R = cfg.T * cfg.k
+    xp = torch.empty((R, cfg.d_model), dtype=torch.bfloat16, device="cuda")
+    scratch = {n: torch.empty_like(torch.as_tensor(routing[n]).cuda()) for n in ("counts", "offsets", "perm", "inv_perm")}
+    B.moe_permute(ctx, torch.as_tensor(routing["topk_idx"]).cuda(), cfg.T, scratch["counts"], scratch["offsets"],
+                  scratch["perm"], scratch["inv_perm"], L["x"], xp)
+    yp = torch.empty((R, cfg.d_model), dtype=torch.bfloat16, device="cuda")
+    B.moe_profile_begin(ctx, 2)
+    for _ in range(2):
+        B.moe_expert_ffn(ctx, xp, scratch["offsets"], R, L["W1"], L["W3"], L["W2"], yp)
+    torch.cuda.synchronize()
+    stage_ms, launches, calls = B.moe_profile_end(ctx)
+    assert calls == 2 and launches["gateup"] == 2 and launches["down"] == 2
+    assert stage_ms["gateup"] > 0 and stage_ms["down"] > 0
+    assert all(stage_ms[n] == 0 for n in ("route", "permute", "gather", "combine"))
+    ctx.close()
+
+
 def test_permute_drops_out_of_range_experts():
     """An expert index outside [0, E) is dropped from every group: inv_perm = -1, counts and
     offsets only cover the valid ids, and the remaining ids keep their stable order."""
