@@ -88,21 +88,53 @@ int launch_ring(const GemmEnv& env, const moe_bf16* A, const moe_bf16* B0, const
 }
 
 // Tile configuration by average rows per expert. All configurations give identical bits.
-int pick_config(const GemmEnv& env, int R, int E) {
+int pick_config(const GemmEnv& env, int R, int E, int nt_large, int nt_mid) {
     if (env.forced_config >= 0) return env.forced_config;
-    // 0: pipelined 256x256 tiles. 1: 128-row tiles (generic kernel). 2: a few dozen rows per
-    // expert (64-row tiles). 3: a handful (32-row tiles, deep weight ring). Between 0 and 1 the padded rows decide: groups a little above a multiple
-    // of 256 rows waste most of a large tile. Per-expert counts are not known on the host, so
-    // the choice prices the average group plus two standard deviations of a uniform routing,
-    // and the large tiles at 0.8 of the time per padded row of the 128-row ones (measured on
-    // micro-batches of 64 to 4096 tokens at the 8x22B shape).
+    // 0: pipelined 256-row tiles (with half-height tails). 1: 128-row tiles (generic kernel).
+    // 2: a few dozen rows per expert (64-row tiles). 3: a handful (32-row tiles, deep weight
+    // ring). Per-expert counts are not known on the host, so the choice prices a uniform routing:
+    // the average group and its standard deviation.
     const double avg = static_cast<double>(R) / (E > 0 ? E : 1);
-    const double upper = avg + 2.0 * std::sqrt(avg);
+    const double sigma = std::sqrt(avg);
+    const double upper = avg + 2.0 * sigma;
     if (upper <= 32.0) return 3;
     if (avg <= 32.0) return 2;
-    const double padded_large = std::ceil(upper / 256.0) * 256.0;
-    const double padded_mid = std::ceil(upper / 128.0) * 128.0;
-    return padded_large * 0.8 <= padded_mid ? 0 : 1;
+    if (upper <= 256.0) {
+        // one row tile per expert either way: the padded rows decide, the large tiles priced at
+        // 0.8 of the time per padded row of the 128-row ones (measured on micro-batches of 64 to
+        // 512 tokens at the 8x22B shape)
+        const double padded_mid = std::ceil(upper / 128.0) * 128.0;
+        return 256.0 * 0.8 <= padded_mid ? 0 : 1;
+    }
+    // Several row tiles per expert. Launch time in units of one full 256-row tile, for groups
+    // one standard deviation below and above the mean: a large tile costs 1, a tail of at most
+    // 128 rows 0.55 (half-height tile), a 128-row tile of the generic kernel 0.8. A launch of
+    // many rounds of tiles (one workgroup per compute unit) costs its tiles; one of fewer than
+    // four rounds costs whole rounds, a last round under half full 0.55 with the large tiles
+    // (it is split), and the large tiles 1.25 times their count then (fewer, longer tiles
+    // balance worse). Measured on micro-batches of 1024 and 2048 tokens at the 8x22B shape,
+    // where the two GEMMs of one call want different answers.
+    const int cus = compute_units(env.device);
+    double units0 = 0.0, tiles0 = 0.0, tiles1 = 0.0;
+    for (const double m : {std::max(1.0, avg - sigma), avg + sigma}) {
+        const double full = std::floor(m / 256.0), tail = m - full * 256.0;
+        units0 += 0.5 * (full + (tail <= 0.0 ? 0.0 : tail <= 128.0 ? 0.55 : 1.0));
+        tiles0 += 0.5 * std::ceil(m / 256.0);
+        tiles1 += 0.5 * std::ceil(m / 128.0);
+    }
+    const double scale0 = static_cast<double>(E) * nt_large, scale1 = static_cast<double>(E) * nt_mid;
+    units0 *= scale0;
+    tiles0 *= scale0;
+    tiles1 *= scale1;
+    double t0, t1;
+    if (tiles0 >= 4.0 * cus) {
+        t0 = units0 / cus;
+    } else {
+        const double whole = std::floor(tiles0 / cus), rem = tiles0 - whole * cus;
+        t0 = 1.25 * (whole + (rem <= 0.0 ? 0.0 : rem <= 0.5 * cus ? 0.55 : 1.0));
+    }
+    t1 = 0.8 * (tiles1 >= 4.0 * cus ? tiles1 / cus : std::ceil(tiles1 / cus));
+    return t0 <= t1 ? 0 : 1;
 }
 
 // Large tiles: four wavefronts of 128 x 128 outputs (one per SIMD) or eight of 128 x 64. The
@@ -159,7 +191,7 @@ int launch_gateup(const GemmEnv& env, const moe_bf16* a, const int32_t* row_inde
                   const moe_bf16* W1, const moe_bf16* W3, moe_bf16* H, hipStream_t s) {
     if (R == 0) return MOE_OK;
     const moe_bf16* x_perm = a;
-    int config = pick_config(env, R_hint, E);
+    int config = pick_config(env, R_hint, E, f / 128, f / 128);
     if (config == 0 && d / 64 < 3) config = 1;     // the pipelined kernel needs three k-steps
     switch (config) {
         case 0:
@@ -188,7 +220,8 @@ template <bool F32>
 int launch_down_as(const GemmEnv& env, const moe_bf16* H, const int32_t* offsets, int R, int R_hint,
                    int d, int f, int E, const moe_bf16* W2, moe_bf16* y_perm, hipStream_t s) {
     if (R == 0) return MOE_OK;
-    int config = pick_config(env, R_hint, E);
+    const bool wide_mid = static_cast<long long>(E) * (d / 256) >= 160 && d % 256 == 0;
+    int config = pick_config(env, R_hint, E, d / 256, wide_mid ? d / 256 : d / 128);
     if (config == 0 && f / 64 < 3) config = 1;     // the pipelined kernel needs three k-steps
     switch (config) {
         case 0:
@@ -198,7 +231,7 @@ int launch_down_as(const GemmEnv& env, const moe_bf16* H, const int32_t* offsets
         case 1:
             // HBM-bound: wide tiles stream more bytes per workgroup, but only if there are
             // enough of them to occupy the 256 compute units (about one m-tile per expert).
-            if (static_cast<long long>(E) * (d / 256) >= 160 && d % 256 == 0) {
+            if (wide_mid) {
                 if (single_m_tile(env, R_hint, E, 128))
                     return launch_grouped<Out<F32, DownMidWideS>>(env, H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
                 return launch_grouped<Out<F32, DownMidWide>>(env, H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
