@@ -9,6 +9,7 @@ namespace moe {
 
 constexpr int kWave = 64;        // CDNA wavefront width
 constexpr int kMaxExperts = 256; // four experts per lane in the permutation and routing kernels
+constexpr int kXcds = 8;         // workgroups are dealt round-robin to the 8 XCDs (own L2 each)
 
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) {
     return __uint_as_float(static_cast<uint32_t>(b) << 16);

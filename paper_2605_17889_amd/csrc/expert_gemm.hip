@@ -50,7 +50,7 @@ int launch_tiles(const GemmEnv& env, std::atomic<uint64_t>& attr_set, Kernel ker
             return MOE_ERR_HIP;
         attr_set.fetch_or(bit, std::memory_order_release);
     }
-    grid = (grid + gemm::kXcds - 1) / gemm::kXcds * gemm::kXcds;
+    grid = (grid + kXcds - 1) / kXcds * kXcds;
     if (grid > 0x7fffffffLL) return MOE_ERR_UNSUPPORTED_SHAPE;
     hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(grid)), dim3(threads), smem, s, args...);
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
@@ -81,7 +81,7 @@ int launch_ring(const GemmEnv& env, const moe_bf16* A, const moe_bf16* B0, const
     const int cus = env.split_last_round ? compute_units(env.device) : 0;
     const long long max_mt = R / Cfg::BM + E;                  // >= sum_e ceil(M_e / BM)
     // split tiles take two slots each: at most ceil(cus / 2 / 8) more slots in every XCD's range
-    const long long grid = max_mt * (N / Cfg::BN_OUT) + gemm::kXcds * ((cus / 2 + gemm::kXcds - 1) / gemm::kXcds + 1);
+    const long long grid = max_mt * (N / Cfg::BN_OUT) + kXcds * ((cus / 2 + kXcds - 1) / kXcds + 1);
     return launch_tiles(env, attr_set, gemm::grouped_gemm_ring_kernel<Cfg, HalfCfg, NA, NB>,
                         gemm::RingCfg<Cfg, NA, NB>::SMEM, Cfg::NTHREADS, grid, s, A, B0, B1, C,
                         offsets, row_index, index_div, E, N, K, cus);

@@ -34,7 +34,6 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kXcds = 8;     // workgroups are dealt round-robin to the 8 XCDs (own L2 each)
 constexpr int kGroupM = 8;   // at most this many m-tiles that sweep the n-tiles together (share weight tiles)
 
 struct TileCoord {

@@ -9,6 +9,8 @@
 // each (token, expert) accumulator sees exactly that order.
 //
 // HBM traffic per token: 2*d_model bytes of x read, 8*k bytes written.
+#include <algorithm>
+#include <atomic>
 #include <type_traits>
 
 #include "common.h"
@@ -451,6 +453,235 @@ __global__ __launch_bounds__(256, 2) void route_logits_group_kernel(const uint16
             bias != nullptr ? acc[0] + bias[e0 + e] : acc[0];
 }
 
+// Logits of 16 tokens x 16 experts per wavefront on the matrix cores, for E a multiple of 16.
+//
+// v_mfma_f32_16x16x1_4b_f32 performs four independent rank-1 updates D_b = a_b * b_b^T + C_b of
+// 16x16 tiles, each element one fused multiply-add, round to nearest even, denormals kept: the
+// same operation as the fmaf of the definition above, at twice the rate of the vector unit.
+// Block b of instruction slot q carries partial sum l = 4*q + b of every (token, expert) pair of
+// the tile, so the 16 slots x 4 blocks hold all 64 partial chains (256 accumulator registers),
+// and the updates of one chain are issued in the defined order (chunk j ascending, then
+// v ascending). The 64 partials of a pair end in ONE lane, where the butterfly
+// s = 32, ..., 1 becomes a tree of plain additions p[l] + p[l + s] (a + b == b + a bitwise).
+//
+// Operands: lane (b, i) = (lane / 16, lane % 16) supplies x[token i][512 j + 8 (4 q + b) + v]
+// as the A value of slot q, step v, and lane (b, n) supplies W_r[512 j + 8 (4 q + b) + v][e0 + n]
+// as the B value. Both come through LDS by direct-to-LDS loads of whole cache lines, half a
+// chunk (256 elements = slots 8 hh .. 8 hh + 7) per stage, three stages in a ring, the loads of
+// half-chunk h + 2 issued between the matrix instructions of half-chunk h:
+//   * W_r: the 256 x 16 slice of a stage is shared by the four wavefronts (four token groups,
+//     one expert group), stored as [slot][step v][lane] so that an operand fetch is one
+//     conflict-free 4-byte read per lane; wavefront w brings in slots 2w, 2w+1;
+//   * x: every wavefront brings in its own 16 token rows, two rows per load, 16-byte pieces of
+//     the two rows interleaved and 32 bytes of padding after each pair, which makes the 16-byte
+//     operand reads (row i, piece 4 q' + b) conflict-free.
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+struct RouteMfma {
+    static constexpr int W_BYTES = 8 * 8 * 64 * 4;          // 16 KB: W_r slice of half a chunk
+    static constexpr int X_PAIR = 1024 + 32;                // two token rows of 512 bytes + padding
+    static constexpr int X_WAVE = 8 * X_PAIR;               // 16 token rows of one wavefront
+    static constexpr int STAGE = W_BYTES + 4 * X_WAVE;      // 50176 bytes
+    static constexpr int NSTAGE = 3;
+    static constexpr int SMEM = NSTAGE * STAGE;             // 150528 bytes
+    static constexpr int LOADS = 12;                        // per wavefront and stage: 8 of x, 4 of W_r
+};
+
+// no "memory" clobber: ordinary LDS reads may move across these loads; the barriers and the
+// counter waits around the stages (which do clobber memory) order what must be ordered
+__device__ __forceinline__ void dma16_to_lds(const void* sbase, uint32_t voff, uint32_t lds_off) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(lds_off), "v"(voff), "s"(sbase) : "m0");
+}
+
+__global__ __launch_bounds__(256) void route_logits_mfma_kernel(const uint16_t* __restrict__ x,
+                                                                const float* __restrict__ wr,
+                                                                const float* __restrict__ bias,
+                                                                int T, int d, int E,
+                                                                float* __restrict__ logits_out) {
+    using R = RouteMfma;
+    extern __shared__ __attribute__((aligned(1024))) unsigned char rsm[];
+
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int groups = E / 16, halves = d / 256;
+    // A tile is one 64-token block x one group of 16 experts. Tiles are numbered so that the
+    // E/16 groups of one token block are consecutive tiles of ONE XCD (workgroups are dealt to
+    // the 8 XCDs in turn): the block's token rows come from HBM once and from that XCD's L2 for
+    // the other groups. A workgroup takes tiles blockIdx.x, blockIdx.x + gridDim.x, ... (the
+    // grid is a multiple of 8, so it stays on its XCD's tiles); a token block past T ends its
+    // list, since every later tile of the list has a higher token block.
+    auto decode = [&](int id, int& tb, int& e0) {
+        const int in_xcd = id / kXcds;
+        tb = (in_xcd / groups) * kXcds + id % kXcds;
+        e0 = (in_xcd % groups) * 16;
+    };
+    int tile = blockIdx.x, tb, e0;
+    decode(tile, tb, e0);
+    if (tb * 64 >= T) return;                             // uniform for the workgroup
+
+    // Loads of the tile that the ring is being filled for (the "target"): x load m covers token
+    // rows 2m, 2m+1 of the wavefront (rows past T read the last row; never stored), lane -> row
+    // 2m + lane%2, 16-byte piece lane/2 of the half-chunk; offsets are relative to the token
+    // block's first row, which goes into the scalar base. W_r load mm covers (slot, step) pairs
+    // 4*(4*wave + mm) .. +3, one per 16 lanes; inside a pair lane%16 = 4*b + (16-byte piece of
+    // the 16 experts); the group's first expert goes into the scalar base.
+    uint32_t x_voff[8], w_voff[4];
+    const uint16_t* x_base;
+    const float* w_base;
+    auto set_target = [&](int ttb, int te0) {
+#pragma unroll
+        for (int m = 0; m < 8; ++m) {
+            const int row = min(ttb * 64 + wave * 16 + 2 * m + (lane & 1), T - 1) - ttb * 64;
+            x_voff[m] = static_cast<uint32_t>(row) * d * 2u + 16u * (lane >> 1);
+        }
+        x_base = x + static_cast<size_t>(ttb) * 64 * d;
+        w_base = wr + te0;
+    };
+#pragma unroll
+    for (int mm = 0; mm < 4; ++mm) {
+        const int pair = 4 * (4 * wave + mm) + (lane >> 4), q = pair >> 3, v = pair & 7, b = (lane & 15) >> 2;
+        w_voff[mm] = (static_cast<uint32_t>(8 * (4 * q + b) + v) * E + 4 * (lane & 3)) * 4u;
+    }
+    const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(rsm));
+    // load n (0..11) of the target's half-chunk h into stage st
+    auto issue = [&](int n, int h, int st) {
+        const uint32_t sb = lds0 + st * R::STAGE;
+        if (n < 8)
+            dma16_to_lds(x_base + 256 * h, x_voff[n], sb + R::W_BYTES + wave * R::X_WAVE + n * R::X_PAIR);
+        else
+            dma16_to_lds(w_base + static_cast<size_t>(256 * h) * E, w_voff[n - 8],
+                         sb + (4 * wave + n - 8) * 1024);
+    };
+    set_target(tb, e0);
+#pragma unroll
+    for (int n = 0; n < R::LOADS; ++n) issue(n, 0, 0);
+#pragma unroll
+    for (int n = 0; n < R::LOADS; ++n) issue(n, 1, 1);
+
+    // operand addresses of this lane inside a stage
+    const int ab = lane >> 4, ai = lane & 15;
+    const uint32_t x_off = R::W_BYTES + wave * R::X_WAVE + (ai >> 1) * R::X_PAIR + 32 * ab + 16 * (ai & 1);
+    const uint32_t w_off = lane * 4;
+
+    f32x16 acc[16];
+    // One half-chunk (slots 8*(h%2) .. +7, steps v = 0..7) from stage st, while the 12 loads of
+    // the target's half-chunk th go to stage stn between the matrix instructions. A turn always
+    // issues 12 loads (past the end of the work: the last half-chunk again, into a stage nobody
+    // reads), so the counter wait at its top is the same on every turn. The results stored
+    // between two turns may complete before older loads: 12 outstanding operations or fewer
+    // still means that the 12 oldest loads, the stage about to be read, have landed.
+    auto turn = [&](int st, int th, int stn, auto odd) {
+        constexpr int Q0 = decltype(odd)::value ? 8 : 0;
+        asm volatile("s_waitcnt vmcnt(%0)" :: "n"(R::LOADS) : "memory");   // this stage has landed
+        __syncthreads();                     // ... for everyone; nobody still reads the stage before
+        const unsigned char* sb = rsm + st * R::STAGE;
+        u32x4 xv[8];
+#pragma unroll
+        for (int ql = 0; ql < 8; ++ql) xv[ql] = *reinterpret_cast<const u32x4*>(sb + x_off + 128 * ql);
+        float wv[16][4];
+        auto read_w = [&](int sidx) {
+#pragma unroll
+            for (int qq = 0; qq < 4; ++qq)
+                wv[sidx][qq] = *reinterpret_cast<const float*>(
+                    sb + w_off + ((4 * (sidx / 8) + qq) * 8 + sidx % 8) * 256);
+        };
+        // The bf16 -> fp32 widening of a step's four token values is done a step ahead, into
+        // registers of its own: a matrix instruction whose operand was written just before it
+        // (or whose operand register the next conversion wants) would wait for the vector unit,
+        // and with one wavefront per SIMD nothing else fills that time.
+        float xf[16][4];
+        auto widen = [&](int sidx) {
+            const int v = sidx % 8;
+#pragma unroll
+            for (int qq = 0; qq < 4; ++qq) {
+                const uint32_t word = xv[4 * (sidx / 8) + qq][v >> 1];
+                xf[sidx][qq] = __uint_as_float((v & 1) ? (word & 0xffff0000u) : (word << 16));
+            }
+        };
+        read_w(0);
+        read_w(1);
+        widen(0);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int sidx = 0; sidx < 16; ++sidx) {          // (slot group, step) = (sidx / 8, sidx % 8)
+            if (sidx + 2 < 16) read_w(sidx + 2);         // operands two steps ahead
+            if (sidx + 1 < 16) widen(sidx + 1);
+#pragma unroll
+            for (int qq = 0; qq < 4; ++qq) {
+                const int ql = 4 * (sidx / 8) + qq;
+                acc[Q0 + ql] = __builtin_amdgcn_mfma_f32_16x16x1f32(xf[sidx][qq], wv[sidx][qq], acc[Q0 + ql], 0, 0, 0);
+            }
+            if (sidx < R::LOADS) issue(sidx, th, stn);
+            // order inside the step: operand reads, the widenings for the next step, then the
+            // four matrix instructions (whose operands were all produced a step ago)
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    int st = 0;                                           // stage of the next turn
+    for (;;) {
+        int ntb, ne0;
+        decode(tile + gridDim.x, ntb, ne0);
+        const bool has_next = ntb * 64 < T;
+#pragma unroll
+        for (int q = 0; q < 16; ++q)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[q][r] = 0.f;
+        for (int h = 0; h < halves; h += 2) {
+            const bool last = h + 2 == halves;
+            if (last && has_next) set_target(ntb, ne0);  // the ring moves on to the next tile
+            const int th0 = !last ? h + 2 : has_next ? 0 : halves - 1;
+            const int th1 = !last ? h + 3 : has_next ? 1 : halves - 1;
+            const int st1 = st == 2 ? 0 : st + 1, st2 = st1 == 2 ? 0 : st1 + 1;
+            turn(st, th0, st2, std::false_type{});
+            turn(st1, th1, st, std::true_type{});
+            st = st2;
+        }
+        // Register 4*b + r of slot q: partial l = 4*q + b of token 4*(lane/16) + r, expert lane%16.
+        // Straight-line code, one token after the other (64 partials in registers at a time).
+        float res[4];
+        float prev = 0.f;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            // An empty statement that "uses" the previous token's result and "redefines" the
+            // accumulators: the compiler cannot start this token's 64 register reads before
+            // the previous token's tree is done (all four at once need more registers than
+            // there are).
+            asm volatile("" : "+a"(acc[0]), "+a"(acc[1]), "+a"(acc[2]), "+a"(acc[3]), "+a"(acc[4]),
+                              "+a"(acc[5]), "+a"(acc[6]), "+a"(acc[7]), "+a"(acc[8]), "+a"(acc[9]),
+                              "+a"(acc[10]), "+a"(acc[11]), "+a"(acc[12]), "+a"(acc[13]),
+                              "+a"(acc[14]), "+a"(acc[15]) : "v"(prev));
+            float p[64];
+#pragma unroll
+            for (int q = 0; q < 16; ++q)
+#pragma unroll
+                for (int b = 0; b < 4; ++b) p[4 * q + b] = acc[q][4 * b + r];
+#pragma unroll
+            for (int s = 32; s >= 1; s >>= 1)
+#pragma unroll
+                for (int l = 0; l < s; ++l) p[l] = p[l] + p[l + s];
+            res[r] = p[0];
+            prev = p[0];
+        }
+        const int e = e0 + (lane & 15);
+        const float be = bias != nullptr ? bias[e] : 0.f;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int t = tb * 64 + wave * 16 + 4 * (lane >> 4) + r;
+            if (t < T) logits_out[static_cast<size_t>(t) * E + e] = bias != nullptr ? res[r] + be : res[r];
+        }
+        if (!has_next) break;
+        tile += gridDim.x;
+        tb = ntb;
+        e0 = ne0;
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // no load may still target LDS at the end
+}
+
 template <int E_, int TOK, int WAVES>
 int launch_route_lds(const moe_bf16* x, const float* wr, const float* bias, int T, int d, int k,
                      int32_t* idx, float* w, float* logits_out, hipStream_t s) {
@@ -506,7 +737,30 @@ int launch_route(const moe_bf16* x, const float* w_router, const float* bias, in
         if (!logits) return MOE_ERR_INVALID_ARG;
         constexpr int TOK = 4;
         const dim3 grid((T + 4 * TOK - 1) / (4 * TOK), (E + 15) / 16);
-        if (E % 16 == 0)     // every group full and 16-byte aligned: vector loads of W_r
+        // Full groups and at least one 64-token block per compute unit and expert group: the
+        // matrix-core form (its 256-accumulator wavefronts leave too few tokens in flight below that)
+        if (E % 16 == 0 && static_cast<long long>((T + 63) / 64) * (E / 16) >= 256) {
+            int device = 0;
+            if (hipGetDevice(&device) != hipSuccess || device < 0 || device >= 64) return MOE_ERR_HIP;
+            static std::atomic<uint64_t> attr_set{0};     // one bit per device, as for the GEMM kernels
+            if (!(attr_set.load(std::memory_order_acquire) & (1ull << device))) {
+                if (hipFuncSetAttribute(reinterpret_cast<const void*>(route_logits_mfma_kernel),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize,
+                                        RouteMfma::SMEM) != hipSuccess)
+                    return MOE_ERR_HIP;
+                attr_set.fetch_or(1ull << device, std::memory_order_release);
+            }
+            // one workgroup per compute unit (LDS and registers allow no more), each working
+            // through its share of the tiles with the operand ring running across tile borders
+            const long long tiles = static_cast<long long>(((T + 63) / 64 + kXcds - 1) / kXcds) * kXcds * (E / 16);
+            int cus = 0;
+            if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess)
+                return MOE_ERR_HIP;
+            const long long grid = std::min<long long>(tiles, std::max(kXcds, cus / kXcds * kXcds));
+            hipLaunchKernelGGL(route_logits_mfma_kernel, dim3(static_cast<unsigned>(grid)),
+                               dim3(256), RouteMfma::SMEM, s, x, w_router, bias, T, d, E, logits);
+        }
+        else if (E % 16 == 0)     // every group full and 16-byte aligned: vector loads of W_r
             hipLaunchKernelGGL((route_logits_group_kernel<TOK, true>), grid, dim3(256), 0, s, x,
                                w_router, bias, T, d, E, logits);
         else

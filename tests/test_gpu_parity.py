@@ -71,6 +71,9 @@ def rand_bits(rng, shape, std):
     # more than 64 experts: logits in passes of 64 experts, selection by one wavefront per token
     (70, 2048, 128, 8, True), (33, 512, 65, 3, False), (21, 1024, 200, 10, True),
     (9, 512, 256, 64, False), (130, 512, 129, 1, True),
+    # enough 64-token blocks x expert groups of 16 for the matrix-core logits kernel, ragged T
+    (2085, 1024, 128, 8, True), (1040, 512, 256, 6, False), (4100, 512, 64, 6, True),
+    (8195, 1536, 32, 4, False), (2048, 512, 128, 2, False),
 ])
 def test_route_bit_exact(T, d, E, k, use_bias):
     say(f"route T={T} d={d} E={E} k={k} bias={use_bias}")
@@ -98,6 +101,38 @@ def test_route_bit_exact(T, d, E, k, use_bias):
     B.moe_route_from_logits(ctx, lg, T, idx2, g2)
     torch.cuda.synchronize()
     assert torch.equal(idx2, idx) and torch.equal(g2, g)
+    ctx.close()
+
+
+def test_route_matrix_core_logits_extreme_values():
+    """The matrix-core logits kernel (E a multiple of 16, many tokens) must round every
+    multiply-add like fmaf, denormal products and sums, signed zeros and wide exponent ranges
+    included: the logits are compared bit for bit with the oracle."""
+    T, d, E, k = 2085, 512, 128, 4
+    rng = np.random.default_rng(77)
+    x = rng.normal(0, 1.0, size=(T, d)).astype(np.float32)
+    wr = rng.normal(0, 1.0, size=(d, E)).astype(np.float32)
+    # rows 0..699: products and sums in the denormal range; 700..1399: exponents spread over
+    # 2^-40..2^40 per element (heavy cancellation); the rest ordinary with planted zeros
+    x[:700] *= 2.0 ** -70
+    x[700:1400] *= np.exp2(rng.integers(-40, 41, size=(700, d))).astype(np.float32)
+    x[1400:][rng.random((T - 1400, d)) < 0.2] = 0.0
+    x[1400:][rng.random((T - 1400, d)) < 0.05] = -0.0
+    wr[:, :64] *= 2.0 ** -70                      # with rows 0..699: products near 2^-140
+    wr[rng.random((d, E)) < 0.1] = 0.0
+    xb = bits(torch.tensor(x).bfloat16())
+    lg_ref = ref.logits(xb, wr, None)
+    assert np.any((lg_ref != 0) & (np.abs(lg_ref) < 1.1754944e-38))       # denormal logits present
+    ctx = B.MoeContext(T, d, 256, E, k)
+    idx = torch.empty((T, k), dtype=torch.int32, device="cuda")
+    g = torch.empty((T, k), dtype=torch.float32, device="cuda")
+    lg = torch.empty((T, E), dtype=torch.float32, device="cuda")
+    B.moe_route(ctx, dev(bf16_tensor_from_bits(xb)), dev(wr), None, T, idx, g, lg)
+    torch.cuda.synchronize()
+    got = lg.cpu().numpy()
+    assert np.array_equal(got.view(np.uint32), lg_ref.view(np.uint32))
+    idx_ref, _ = ref.topk(lg_ref, k)
+    assert np.array_equal(idx.cpu().numpy(), idx_ref)
     ctx.close()
 
 
