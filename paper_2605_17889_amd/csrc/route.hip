@@ -159,55 +159,75 @@ __global__ __launch_bounds__(256) void route_kernel(const uint16_t* __restrict__
     }
 }
 
-// Selection and gates for more than 64 experts: one wavefront per token, lane l holds the
-// logits of experts l, l+64, l+128, l+192. Each of the k rounds takes the largest remaining
-// logit of the wavefront (ties -> lower expert index, NaN below every number) by a butterfly
-// of (value, index) pairs; the gates are the softmax over the selected logits, accumulated in
-// slot order like select_and_gate().
+// Selection and gates for more than 16 experts: 16 lanes per token (four tokens per wavefront),
+// lane g of a token's group holds the logits of experts g, g+16, g+32, ... (EW of them). Each of
+// the k rounds takes the largest remaining logit of the group (ties -> lower expert index, NaN
+// below every number): first inside the lane, ascending, then by four exchange steps of
+// (value, index) pairs over the 16 lanes; "larger value, then lower index" is a total order, so
+// the result does not depend on how the lanes are paired. The gates are the softmax over the selected logits,
+// accumulated in slot order like select_and_gate().
+template <int EW>
 __global__ __launch_bounds__(256) void route_select_kernel(const float* __restrict__ logits, int T,
                                                            int E, int k,
                                                            int32_t* __restrict__ topk_idx,
                                                            float* __restrict__ topk_w) {
-    constexpr int EW = kMaxExperts / kWave;
-    const int lane = threadIdx.x & (kWave - 1);
-    const int t = (blockIdx.x * blockDim.x + threadIdx.x) / kWave;
-    if (t >= T) return;
+    constexpr int G = 16;
+    const int g = threadIdx.x & (G - 1);
+    const int t = (blockIdx.x * blockDim.x + threadIdx.x) / G;
+    const bool live = t < T;                              // whole groups; shuffles stay in a group
     float v[EW];
 #pragma unroll
     for (int w = 0; w < EW; ++w) {
-        const int e = w * kWave + lane;
-        float l = (e < E) ? logits[static_cast<size_t>(t) * E + e] : -INFINITY;
+        const int e = w * G + g;
+        const float l = (live && e < E) ? logits[static_cast<size_t>(t) * E + e] : -INFINITY;
         v[w] = (l != l) ? -INFINITY : l;
     }
-    unsigned taken = 0;                                   // bit w: expert w*64+lane is selected
-    float top = 0.f, den = 0.f, my_w = 0.f;              // lane s keeps the weight of slot s
-    int my_idx = 0;
+    unsigned taken = 0;                                   // bit w: expert w*16+g is selected
+    float top = 0.f, den = 0.f;
+    float my_w[4] = {0.f, 0.f, 0.f, 0.f};                 // lane g keeps slots g, g+16, g+32, g+48
+    int my_idx[4] = {0, 0, 0, 0};
     for (int s = 0; s < k; ++s) {
         // best of this lane: ascending expert index, strict '>' keeps the lower index on ties
         float bv = 0.f;
         int be = -1;
 #pragma unroll
         for (int w = 0; w < EW; ++w) {
-            const int e = w * kWave + lane;
+            const int e = w * G + g;
             if (e < E && !((taken >> w) & 1u) && (be < 0 || v[w] > bv)) { bv = v[w]; be = e; }
         }
-        // best of the wavefront: larger value, then lower index; lanes without a candidate lose
-#pragma unroll
-        for (int m = 32; m >= 1; m >>= 1) {
-            const float ov = __shfl_xor(bv, m, kWave);
-            const int oe = __shfl_xor(be, m, kWave);
+        // best of the group: larger value, then lower index; lanes without a candidate lose
+        // (data-parallel-primitive moves inside a row of 16 lanes: rotate by 8, by 4, then swap
+        // inside quads at distance 2 and 1; after the four steps every lane has seen all 16)
+        auto take = [&](float ov, int oe) {
             const bool other = oe >= 0 && (be < 0 || ov > bv || (ov == bv && oe < be));
             if (other) { bv = ov; be = oe; }
-        }
-        if ((be & (kWave - 1)) == lane) taken |= 1u << (be >> 6);   // be >= 0 because k <= E
+        };
+#define MOE_DPP_STEP(CTRL)                                                                        \
+        take(__int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(bv), CTRL, 0xf, 0xf, false)), \
+             __builtin_amdgcn_update_dpp(0, be, CTRL, 0xf, 0xf, false))
+        MOE_DPP_STEP(0x128);      // row_ror:8
+        MOE_DPP_STEP(0x124);      // row_ror:4
+        MOE_DPP_STEP(0x4e);       // quad_perm:[2,3,0,1]
+        MOE_DPP_STEP(0xb1);       // quad_perm:[1,0,3,2]
+#undef MOE_DPP_STEP
+        if ((be & (G - 1)) == g) taken |= 1u << (be >> 4);    // be >= 0 because k <= E
         if (s == 0) top = bv;
         const float w = expf(bv - top);
         den += w;
-        if (lane == s) { my_w = w; my_idx = be; }             // k <= 64: one slot per lane
+        if ((s & (G - 1)) == g) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if ((s >> 4) == j) { my_w[j] = w; my_idx[j] = be; }
+        }
     }
-    if (lane < k) {
-        topk_idx[static_cast<size_t>(t) * k + lane] = my_idx;
-        topk_w[static_cast<size_t>(t) * k + lane] = my_w / den;
+    if (!live) return;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int s = j * G + g;
+        if (s < k) {
+            topk_idx[static_cast<size_t>(t) * k + s] = my_idx[j];
+            topk_w[static_cast<size_t>(t) * k + s] = my_w[j] / den;
+        }
     }
 }
 
@@ -716,10 +736,17 @@ int launch_route_t(const moe_bf16* x, const float* wr, const float* bias, int T,
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
 
-int launch_select_wave(const float* logits, int T, int E, int k, int32_t* idx, float* w,
-                       hipStream_t s) {
-    const int blocks = (T + 3) / 4;                       // 4 wavefronts = 4 tokens per block
-    hipLaunchKernelGGL(route_select_kernel, dim3(blocks), dim3(256), 0, s, logits, T, E, k, idx, w);
+int launch_select_groups(const float* logits, int T, int E, int k, int32_t* idx, float* w,
+                         hipStream_t s) {
+    const int blocks = (T + 15) / 16;                     // 16 lanes per token, 16 tokens per block
+#define MOE_SEL(EW)                                                                              \
+    hipLaunchKernelGGL((route_select_kernel<EW>), dim3(blocks), dim3(256), 0, s, logits, T, E, k, \
+                       idx, w)
+    if (E <= 32) MOE_SEL(2);
+    else if (E <= 64) MOE_SEL(4);
+    else if (E <= 128) MOE_SEL(8);
+    else MOE_SEL(16);
+#undef MOE_SEL
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
 
@@ -779,15 +806,13 @@ int launch_route(const moe_bf16* x, const float* w_router, const float* bias, in
 int launch_route_from_logits(const float* logits, int T, int E, int k, int32_t* topk_idx,
                              float* topk_w, hipStream_t s) {
     if (T == 0) return MOE_OK;
-    if (E > 64) return launch_select_wave(logits, T, E, k, topk_idx, topk_w, s);
+    if (E > 16) return launch_select_groups(logits, T, E, k, topk_idx, topk_w, s);
     const int blocks = (T + 255) / 256;
 #define MOE_RFL(EP)                                                                              \
     hipLaunchKernelGGL((route_from_logits_kernel<EP>), dim3(blocks), dim3(256), 0, s, logits, T, \
                        E, k, topk_idx, topk_w)
     if (E <= 8) MOE_RFL(8);
-    else if (E <= 16) MOE_RFL(16);
-    else if (E <= 32) MOE_RFL(32);
-    else MOE_RFL(64);
+    else MOE_RFL(16);
 #undef MOE_RFL
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
