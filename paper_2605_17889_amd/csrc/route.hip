@@ -764,9 +764,10 @@ int launch_route(const moe_bf16* x, const float* w_router, const float* bias, in
         if (!logits) return MOE_ERR_INVALID_ARG;
         constexpr int TOK = 4;
         const dim3 grid((T + 4 * TOK - 1) / (4 * TOK), (E + 15) / 16);
-        // Full groups and at least one 64-token block per compute unit and expert group: the
-        // matrix-core form (its 256-accumulator wavefronts leave too few tokens in flight below that)
-        if (E % 16 == 0 && static_cast<long long>((T + 63) / 64) * (E / 16) >= 256) {
+        // Full groups and at least 128 tiles of 64 tokens x 16 experts: the matrix-core form. One
+        // tile takes it about as long as 130 k (token, expert) pairs take the vector-unit
+        // kernel, whatever the number of tiles up to one per compute unit (measured crossover).
+        if (E % 16 == 0 && static_cast<long long>((T + 63) / 64) * (E / 16) >= 128) {
             int device = 0;
             if (hipGetDevice(&device) != hipSuccess || device < 0 || device >= 64) return MOE_ERR_HIP;
             static std::atomic<uint64_t> attr_set{0};     // one bit per device, as for the GEMM kernels
@@ -780,9 +781,14 @@ int launch_route(const moe_bf16* x, const float* w_router, const float* bias, in
             // one workgroup per compute unit (LDS and registers allow no more), each working
             // through its share of the tiles with the operand ring running across tile borders
             const long long tiles = static_cast<long long>(((T + 63) / 64 + kXcds - 1) / kXcds) * kXcds * (E / 16);
-            int cus = 0;
-            if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess)
-                return MOE_ERR_HIP;
+            static std::atomic<int> cus_of[64];           // compute units per device, asked once
+            int cus = cus_of[device].load(std::memory_order_relaxed);
+            if (cus == 0) {
+                if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess ||
+                    cus <= 0)
+                    return MOE_ERR_HIP;
+                cus_of[device].store(cus, std::memory_order_relaxed);
+            }
             const long long grid = std::min<long long>(tiles, std::max(kXcds, cus / kXcds * kXcds));
             hipLaunchKernelGGL(route_logits_mfma_kernel, dim3(static_cast<unsigned>(grid)),
                                dim3(256), RouteMfma::SMEM, s, x, w_router, bias, T, d, E, logits);

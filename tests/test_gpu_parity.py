@@ -73,7 +73,7 @@ def rand_bits(rng, shape, std):
     (9, 512, 256, 64, False), (130, 512, 129, 1, True),
     # enough 64-token blocks x expert groups of 16 for the matrix-core logits kernel, ragged T
     (2085, 1024, 128, 8, True), (1040, 512, 256, 6, False), (4100, 512, 64, 6, True),
-    (8195, 1536, 32, 4, False), (2048, 512, 128, 2, False),
+    (8195, 1536, 32, 4, False), (2048, 512, 128, 2, False), (1000, 512, 128, 8, True),
 ])
 def test_route_bit_exact(T, d, E, k, use_bias):
     say(f"route T={T} d={d} E={E} k={k} bias={use_bias}")
