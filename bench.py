@@ -420,6 +420,7 @@ def main():
             graph.replay()
         torch.cuda.synchronize()
         elapsed = time.perf_counter() - t0
+        per_call = None
         # stage times of one eager pass, for the breakdown only
         B.moe_profile_begin(ctx, 3)
         for _ in range(3):
@@ -436,7 +437,8 @@ def main():
         torch.cuda.synchronize()
         elapsed = time.perf_counter() - t0
         sclk_mhz, board_w = clock.stop()
-        stage_ms, launches, calls = B.moe_profile_end(ctx)
+        per_call, launches, calls = B.moe_profile_end_per_call(ctx, args.steps)
+        stage_ms = {name: sum(c[name] for c in per_call) for name in B.STAGES}
     counts = torch.empty(cfg.E, dtype=torch.int32, device="cuda")
     B.moe_last_routing(ctx, min(T, args.micro) if args.micro > 0 else T, counts=counts)
     torch.cuda.synchronize()
@@ -449,6 +451,10 @@ def main():
         ms = stage_ms[name] / max(calls, 1)
         n_launch = launches[name] / max(calls, 1)
         ent = {"ms_per_step": ms, "launches_per_step": n_launch, "bound": model[name]["bound"]}
+        if per_call:                         # eager timed steps: median and minimum over the steps
+            vals = sorted(c[name] for c in per_call)
+            ent["median_ms"] = vals[len(vals) // 2]
+            ent["min_ms"] = vals[0]
         if ms > 0:
             ent["GB/s"] = model[name]["bytes"] / (ms * 1e-3) / 1e9
             if "flops" in model[name]:

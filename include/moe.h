@@ -208,6 +208,13 @@ int moe_last_routing(moe_ctx* ctx, int32_t T, int32_t* topk_idx, float* topk_w, 
  * covered (*calls), then disarms. Costs two event records per stage while armed. */
 int moe_profile_begin(moe_ctx* ctx, int32_t max_calls);
 int moe_profile_end(moe_ctx* ctx, double* stage_ms, int64_t* stage_launches, int32_t* calls);
+/* The same, per call instead of summed: per_call_ms[c * MOE_NUM_STAGES + stage] (host, room for
+ * capacity_calls calls, zero-filled first) is the time call c spent in that stage (a
+ * micro-batched call adds up its micro-batches); calls beyond capacity_calls are dropped from
+ * the table but still counted in *calls. For medians and minima over the timed steps (paper
+ * Section 5 reports single figures; this library reports mean, median and minimum). */
+int moe_profile_end_per_call(moe_ctx* ctx, double* per_call_ms, int32_t capacity_calls,
+                             int64_t* stage_launches, int32_t* calls);
 
 /* Roofline estimate of the expert stage, host arithmetic only (no GPU is touched).
  * Paper Table 1, row 3: per expert D_X = 2*rows*d_h and D_Y = 6*d_h*d_e operand bytes and

@@ -24,6 +24,7 @@ EXPORTS = (
     "moe_layer_forward_microbatched", "moe_last_routing", "moe_profile_begin", "moe_profile_end",
     "moe_set_gemm_config", "moe_estimate_expert_stage", "moe_layer_forward_streamed",
     "moe_estimate_streamed_stage", "moe_permute_static", "moe_set_expert_output_fp32",
+    "moe_profile_end_per_call",
 )
 
 
@@ -243,6 +244,19 @@ def moe_profile_end(ctx: MoeContext):
     calls = C.c_int32(0)
     _check(lib().moe_profile_end(ctx._h, ms, launches, C.byref(calls)), "moe_profile_end")
     return ({s: ms[i] for i, s in enumerate(STAGES)},
+            {s: launches[i] for i, s in enumerate(STAGES)}, calls.value)
+
+
+def moe_profile_end_per_call(ctx: MoeContext, capacity_calls: int):
+    """-> (list over calls of dict stage -> ms, dict stage -> launches, calls)."""
+    n = len(STAGES)
+    ms = (C.c_double * (n * capacity_calls))()
+    launches = (C.c_int64 * n)()
+    calls = C.c_int32(0)
+    _check(lib().moe_profile_end_per_call(ctx._h, ms, C.c_int32(capacity_calls), launches,
+                                          C.byref(calls)), "moe_profile_end_per_call")
+    got = min(calls.value, capacity_calls)
+    return ([{s: ms[c * n + i] for i, s in enumerate(STAGES)} for c in range(got)],
             {s: launches[i] for i, s in enumerate(STAGES)}, calls.value)
 
 

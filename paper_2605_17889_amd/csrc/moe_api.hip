@@ -29,6 +29,7 @@ struct moe_ctx {
     int prof_max_calls, prof_calls;
     std::vector<hipEvent_t> prof_events;       // per recorded interval: start, stop
     std::vector<int> prof_stage;               // stage of each interval
+    std::vector<int> prof_call;                // armed call (0-based) that the interval belongs to
     int64_t prof_launches[MOE_NUM_STAGES];
     // streamed experts (created by the first moe_layer_forward_streamed call, kept until destroy)
     hipStream_t copy_stream;
@@ -99,6 +100,7 @@ int run_stage(moe_ctx* c, int stage, int launches, hipStream_t s, Fn&& fn) {
         c->prof_events.push_back(e0);
         c->prof_events.push_back(e1);
         c->prof_stage.push_back(stage);
+        c->prof_call.push_back(c->prof_calls - 1);
         c->prof_launches[stage] += launches;
     }
     return rc;
@@ -468,6 +470,7 @@ int moe_profile_begin(moe_ctx* c, int32_t max_calls) {
     for (hipEvent_t e : c->prof_events) (void)hipEventDestroy(e);
     c->prof_events.clear();
     c->prof_stage.clear();
+    c->prof_call.clear();
     for (auto& v : c->prof_launches) v = 0;
     c->prof_armed = true;
     c->prof_max_calls = max_calls;
@@ -475,25 +478,52 @@ int moe_profile_begin(moe_ctx* c, int32_t max_calls) {
     return MOE_OK;
 }
 
-int moe_profile_end(moe_ctx* c, double* stage_ms, int64_t* stage_launches, int32_t* calls) {
-    if (!c || !stage_ms || !stage_launches || !calls) return MOE_ERR_INVALID_ARG;
+namespace {
+// Waits for the recorded intervals and adds every one to its stage's total and, if asked for,
+// to its (call, stage) cell; disarms and releases the events.
+int profile_collect(moe_ctx* c, double* stage_ms, double* per_call_ms, int32_t capacity_calls,
+                    int64_t* stage_launches, int32_t* calls) {
+    if (!c || !stage_launches || !calls) return MOE_ERR_INVALID_ARG;
     if (!c->prof_armed) return MOE_ERR_INVALID_ARG;
     c->prof_armed = false;
-    for (int i = 0; i < MOE_NUM_STAGES; ++i) { stage_ms[i] = 0.0; stage_launches[i] = c->prof_launches[i]; }
+    const int32_t n_calls = c->prof_calls < c->prof_max_calls ? c->prof_calls : c->prof_max_calls;
+    for (int i = 0; i < MOE_NUM_STAGES; ++i) {
+        if (stage_ms) stage_ms[i] = 0.0;
+        stage_launches[i] = c->prof_launches[i];
+    }
+    if (per_call_ms)
+        for (int64_t i = 0; i < static_cast<int64_t>(capacity_calls) * MOE_NUM_STAGES; ++i) per_call_ms[i] = 0.0;
     int rc = MOE_OK;
     for (size_t i = 0; i < c->prof_stage.size(); ++i) {
         hipEvent_t e0 = c->prof_events[2 * i], e1 = c->prof_events[2 * i + 1];
         float ms = 0.f;
-        if (hipEventSynchronize(e1) != hipSuccess || hipEventElapsedTime(&ms, e0, e1) != hipSuccess)
+        if (hipEventSynchronize(e1) != hipSuccess || hipEventElapsedTime(&ms, e0, e1) != hipSuccess) {
             rc = MOE_ERR_HIP;
-        else
-            stage_ms[c->prof_stage[i]] += ms;
+            continue;
+        }
+        if (stage_ms) stage_ms[c->prof_stage[i]] += ms;
+        const int call = c->prof_call[i];
+        if (per_call_ms && call >= 0 && call < capacity_calls)
+            per_call_ms[static_cast<size_t>(call) * MOE_NUM_STAGES + c->prof_stage[i]] += ms;
     }
-    *calls = c->prof_calls < c->prof_max_calls ? c->prof_calls : c->prof_max_calls;
+    *calls = n_calls;
     for (hipEvent_t e : c->prof_events) (void)hipEventDestroy(e);
     c->prof_events.clear();
     c->prof_stage.clear();
+    c->prof_call.clear();
     return rc;
+}
+}  // namespace
+
+int moe_profile_end(moe_ctx* c, double* stage_ms, int64_t* stage_launches, int32_t* calls) {
+    if (!stage_ms) return MOE_ERR_INVALID_ARG;
+    return profile_collect(c, stage_ms, nullptr, 0, stage_launches, calls);
+}
+
+int moe_profile_end_per_call(moe_ctx* c, double* per_call_ms, int32_t capacity_calls,
+                             int64_t* stage_launches, int32_t* calls) {
+    if (!per_call_ms || capacity_calls < 1) return MOE_ERR_INVALID_ARG;
+    return profile_collect(c, nullptr, per_call_ms, capacity_calls, stage_launches, calls);
 }
 
 /* Tuning/testing knob of one context: force the expert-GEMM tile configuration (0 large, 1 medium,

@@ -869,6 +869,15 @@ def test_profile_stage_times_of_layer_and_expert_ffn():
     assert calls == 2 and launches["gateup"] == 2 and launches["down"] == 2
     assert stage_ms["gateup"] > 0 and stage_ms["down"] > 0
     assert all(stage_ms[n] == 0 for n in ("route", "permute", "gather", "combine"))
+    # the same per call: every call has every stage, and the cells add up to the totals' scale
+    B.moe_profile_begin(ctx, 4)
+    for _ in range(4):
+        run_layer(cfg, L, ctx=ctx, micro=100)
+    per_call, launches4, calls4 = B.moe_profile_end_per_call(ctx, 3)      # room for 3 of the 4 calls
+    assert calls4 == 4 and len(per_call) == 3
+    for c in per_call:
+        assert all(c[n] > 0 for n in ("route", "permute", "gateup", "down", "combine")) and c["gather"] == 0
+    assert launches4["gateup"] == 4 * 3                              # 3 micro-batches of <= 100 tokens per call
     ctx.close()
 
 
