@@ -1,6 +1,7 @@
 """GPU parity: the HIP library (through its C ABI) against the CPU oracle on the same seeded
 inputs. Integer outputs must match bit for bit; floating-point outputs within
 rel-L2 <= 1e-2 and max-abs <= 2e-2 * max|y_ref| (bf16 operands, fp32 accumulation)."""
+import dataclasses
 import json
 import os
 import sys
@@ -614,12 +615,16 @@ def test_layer_with_materialised_gather_bitwise(preset):
     ctx.close()
 
 
-def test_layer_replays_from_a_hip_graph():
+@pytest.mark.parametrize("shape", ["tiny", "many_experts"])
+def test_layer_replays_from_a_hip_graph(shape):
     """The layer call only enqueues kernels (no allocation, no memset, no host synchronisation),
     so it can be captured once and replayed: every replay must give the eager result for the
-    input that is in the captured buffer at that time."""
+    input that is in the captured buffer at that time. The second shape (64 experts, 2048
+    tokens) runs the matrix-core router, the 16-lane selection and the many-expert permutation."""
     cfg = synth.PRESETS["tiny"]
-    say("layer tiny captured into a HIP graph, three replays with eager work in between")
+    if shape == "many_experts":
+        cfg = dataclasses.replace(cfg, T=2048, d_model=512, d_ff=256, E=64, k=4)
+    say(f"layer {shape} captured into a HIP graph, three replays with eager work in between")
     L = synth.make_layer(cfg, "cuda")
     T = cfg.T
     ctx = B.MoeContext(T, cfg.d_model, cfg.d_ff, cfg.E, cfg.k)
