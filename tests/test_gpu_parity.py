@@ -137,6 +137,38 @@ def test_route_matrix_core_logits_extreme_values():
     ctx.close()
 
 
+@pytest.mark.parametrize("T,d,E,k", [
+    (2000, 512, 80, 23), (1025, 1536, 160, 56), (3001, 1024, 144, 9), (500, 1536, 256, 3),
+    (2000, 1024, 96, 48), (1023, 1024, 65, 48), (500, 1536, 200, 29), (7, 512, 128, 42),
+])
+def test_route_many_experts_with_duplicate_columns(T, d, E, k):
+    """Expert counts that are multiples of 16 but not powers of two (matrix-core logits where the
+    batch is large enough), odd counts (vector-unit logits), large k, and router columns that are
+    copies of each other, so that every token has exact ties that the selection must break by
+    the lower expert index in every lane arrangement."""
+    say(f"route with tied experts T={T} d={d} E={E} k={k}")
+    rng = np.random.default_rng(T + 7 * E + k)
+    x = rand_bits(rng, (T, d), 1.0)
+    wr = rng.normal(0, 0.02, size=(d, E)).astype(np.float32)
+    src = rng.integers(0, E, size=6)
+    dst = rng.integers(0, E, size=6)
+    wr[:, dst] = wr[:, src]
+    bias = rng.normal(0, 0.3, size=E).astype(np.float32)
+    bias[dst] = bias[src]
+    lg_ref = ref.logits(x, wr, bias)
+    idx_ref, g_ref = ref.topk(lg_ref, k)
+    ctx = B.MoeContext(T, d, 256, E, k)
+    idx = torch.empty((T, k), dtype=torch.int32, device="cuda")
+    g = torch.empty((T, k), dtype=torch.float32, device="cuda")
+    lg = torch.empty((T, E), dtype=torch.float32, device="cuda")
+    B.moe_route(ctx, dev(bf16_tensor_from_bits(x)), dev(wr), dev(bias), T, idx, g, lg)
+    torch.cuda.synchronize()
+    assert np.array_equal(lg.cpu().numpy().view(np.uint32), lg_ref.view(np.uint32))
+    assert np.array_equal(idx.cpu().numpy(), idx_ref)
+    assert np.max(np.abs(g.cpu().numpy() - g_ref)) <= GATE_TOL
+    ctx.close()
+
+
 def test_route_golden_tree_cases_on_gpu():
     cases = json.load(open(os.path.join(GOLD, "route_tree_cases.json")))["cases"]
     hx = lambda s: float.fromhex(s)
