@@ -1,5 +1,7 @@
 // Router: logits, top-k selection and gates (paper Section 2.1: a routing function sends each
-// token to the top-k of the experts). One wavefront owns TOK consecutive tokens.
+// token to the top-k of the experts). In the vector-unit kernels one wavefront owns TOK
+// consecutive tokens; the matrix-core kernel (many experts, many tokens) gives a wavefront a
+// tile of 16 tokens x 16 experts.
 //
 // The fp32 summation order of a logit is fixed so that the selected indices are reproducible
 // bit for bit: lane l of the wavefront owns elements i = 512*j + 8*l + v (one 16-byte vector
@@ -364,7 +366,7 @@ __global__ __launch_bounds__(WAVES * 64) void route_kernel_lds(const uint16_t* _
 // 4*TOK tokens and one group, and stages that group's 512 x 16 slice of W_r per chunk in LDS
 // exactly like route_kernel_lds (rows of W_r are E floats apart here). Every (token, expert)
 // accumulator still sees the canonical order. Only the logits are stored; the selection runs
-// afterwards (route_from_logits_kernel or route_select_kernel).
+// afterwards (route_select_kernel).
 template <int TOK, bool VEC>
 __global__ __launch_bounds__(256, 2) void route_logits_group_kernel(const uint16_t* __restrict__ x,
                                                                  const float* __restrict__ wr,
