@@ -66,11 +66,95 @@ struct TileCoord {
 // the workgroup index. Result: expert >= 0: a tile; kNoTile: the range is exhausted (every later
 // slot is too); kEmptySlot: this slot holds nothing (the lower half of a tile that has none).
 constexpr int kNoTile = -1, kEmptySlot = -2;
+
+// The same map for exactly 8 experts, on the scalar unit: the nine offsets are wavefront-uniform
+// reads of memory that the kernel never writes, so they come through the scalar cache (a hit
+// for every workgroup of a compute unit after the first) and the search is a handful of scalar
+// instructions instead of vector loads, a prefix scan by shuffles and a ballot.
+template <int BM>
+__device__ __forceinline__ TileCoord locate_tile_scalar8(const int32_t* __restrict__ offsets, int NT,
+                                                         int split_cus, int xcd, int slot) {
+    TileCoord tc{kNoTile, 0, 0, 0, 0, 1};
+    int off[9];
+#pragma unroll
+    for (int e = 0; e < 9; ++e) off[e] = offsets[e];
+    int incl[8];
+    int total = 0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        total += ((off[e + 1] - off[e] + BM - 1) / BM) * NT;
+        incl[e] = total;
+    }
+    const int per = (total + kXcds - 1) / kXcds;
+    const int len = max(0, min(per, total - xcd * per));
+    int halved = 0;
+    if (split_cus > 0) {
+        const int rem = total % split_cus;
+        if (rem > 0 && 2 * rem <= split_cus) halved = min(len, (rem + kXcds - 1) / kXcds);
+    }
+    int tile_slot = slot, half = -1;
+    if (slot >= len - halved) {
+        const int j = slot - (len - halved);
+        if (j >= 2 * halved) return tc;
+        tile_slot = len - halved + (j >> 1);
+        half = j & 1;
+    }
+    const int L = xcd * per + tile_slot;
+    if (L >= total) return tc;
+    int e = 0;
+#pragma unroll
+    for (int i = 0; i < 7; ++i) e += (L >= incl[i]) ? 1 : 0;      // first expert whose range holds L
+    int start = 0, m_e = 0, row_e = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+        if (i == e) {
+            start = i == 0 ? 0 : incl[i - 1];
+            m_e = off[i + 1] - off[i];
+            row_e = off[i];
+        }
+    const int mt = (m_e + BM - 1) / BM;
+    const int ngroups = (mt + kGroupM - 1) / kGroupM;
+    const int base = mt / ngroups, extra = mt - base * ngroups;
+    const int local = L - start;
+    const int big = extra * (base + 1) * NT;
+    int gm, head, in;
+    if (local < big) {
+        gm = base + 1;
+        const int g = local / (gm * NT);
+        head = g * gm;
+        in = local - g * (gm * NT);
+    } else {
+        gm = base;
+        const int g = (local - big) / (gm * NT);
+        head = extra * (base + 1) + g * gm;
+        in = local - big - g * (gm * NT);
+    }
+    const int mi = head + in % gm;
+    int row0 = row_e + mi * BM, nrows = min(BM, m_e - mi * BM);
+    if (half >= 0) {
+        const int h0 = half * (BM / 2);
+        if (nrows <= h0) {
+            tc.expert = kEmptySlot;
+            return tc;
+        }
+        row0 += h0;
+        nrows = min(BM / 2, nrows - h0);
+    }
+    tc.expert = e;
+    tc.mi = in % gm;
+    tc.gm = gm;
+    tc.nt = in / gm;
+    tc.row0 = row0;
+    tc.rows = nrows;
+    return tc;
+}
+
 template <int BM>
 __device__ __forceinline__ TileCoord locate_tile_at(const int32_t* __restrict__ offsets, int E,
                                                     int NT, int split_cus, int xcd, int slot) {
     constexpr int EW = kMaxExperts / kWave;
     TileCoord tc{kNoTile, 0, 0, 0, 0, 1};
+    if (E == 8) return locate_tile_scalar8<BM>(offsets, NT, split_cus, xcd, slot);
     const int lane = threadIdx.x & (kWave - 1);
     int rows[EW], first[EW], tiles[EW], incl[EW];     // per expert of this lane; incl: prefix sum
     int carry = 0;
