@@ -269,7 +269,7 @@ int moe_estimate_streamed_stage(const moe_shape* shape, const int32_t* rows, int
 
 /* Tuning / testing knob of ONE context (it lasts until changed; set it from the thread that uses
  * the context): force the expert-GEMM tile configuration
- * (0 = large, 1 = medium, 2 = small, 3 = tiny rows-per-expert tile) or -1 for the automatic choice by
+ * (0 = large, 1 = medium, 2 = small, 3 = tiny rows-per-expert tile, 4 = the 96-row medium tile) or -1 for the automatic choice by
  * average rows per expert. Adding 16 to any of these makes the medium and small tiles load the
  * weights as ordinary (cached) lines, adding 32 as non-temporal ones; without either the library
  * picks non-temporal loads when about every expert has a single row tile (decode), where each

@@ -92,13 +92,16 @@ int pick_config(const GemmEnv& env, int R, int E, int nt_large, int nt_mid) {
     if (env.forced_config >= 0) return env.forced_config;
     // 0: pipelined 256-row tiles (with half-height tails). 1: 128-row tiles (generic kernel).
     // 2: a few dozen rows per expert (64-row tiles). 3: a handful (32-row tiles, deep weight
-    // ring). Per-expert counts are not known on the host, so the choice prices a uniform routing:
-    // the average group and its standard deviation.
+    // ring). 4: 96-row tiles of four wavefronts side by side (groups of 33 to 96 rows: a quarter
+    // fewer matrix instructions and fragment reads per k-step than the 128-row tile, and room
+    // for a deeper weight ring in the down projection). Per-expert counts are not known on the
+    // host, so the choice prices a uniform routing: the average group and its standard deviation.
     const double avg = static_cast<double>(R) / (E > 0 ? E : 1);
     const double sigma = std::sqrt(avg);
     const double upper = avg + 2.0 * sigma;
     if (upper <= 32.0) return 3;
     if (avg <= 32.0) return 2;
+    if (upper <= 96.0) return 4;
     if (upper <= 256.0) {
         // one row tile per expert either way: the padded rows decide, the large tiles priced at
         // 0.8 of the time per padded row of the 128-row ones (measured on micro-batches of 64 to
@@ -173,6 +176,12 @@ using DownMidS     = Config<128, 128, 64, 2, 2, 4, false, true>;
 using DownMidWideS = Config<128, 256, 64, 2, 4, 3, false, true>;
 using DownSmallS   = Config<64, 64, 64, 1, 2, 4, false, true>;
 // a handful of rows per expert (decode): 32-row tiles leave LDS for seven 16 KB weight stages
+using GateUpMid96  = Config<96, 256, 64, 1, 4, 3, true>;
+using GateUpMid96S = Config<96, 256, 64, 1, 4, 3, true, true>;
+using DownMid96      = Config<96, 128, 64, 1, 4, 5, false>;
+using DownMid96S     = Config<96, 128, 64, 1, 4, 5, false, true>;
+using DownMid96Wide  = Config<96, 256, 64, 1, 4, 3, false>;
+using DownMid96WideS = Config<96, 256, 64, 1, 4, 3, false, true>;
 using GateUpTiny   = Config<32, 128, 64, 1, 2, 7, true>;
 using GateUpTinyS  = Config<32, 128, 64, 1, 2, 7, true, true>;
 using DownTiny     = Config<32, 128, 64, 1, 2, 7, false>;
@@ -202,6 +211,10 @@ int launch_gateup(const GemmEnv& env, const moe_bf16* a, const int32_t* row_inde
             if (single_m_tile(env, R_hint, E, 128))
                 return launch_grouped<GateUpMidS>(env, x_perm, W1, W3, H, offsets, row_index, index_div, R, E, f, d, s);
             return launch_grouped<GateUpMid>(env, x_perm, W1, W3, H, offsets, row_index, index_div, R, E, f, d, s);
+        case 4:
+            if (single_m_tile(env, R_hint, E, 96))
+                return launch_grouped<GateUpMid96S>(env, x_perm, W1, W3, H, offsets, row_index, index_div, R, E, f, d, s);
+            return launch_grouped<GateUpMid96>(env, x_perm, W1, W3, H, offsets, row_index, index_div, R, E, f, d, s);
         case 3:
             if (single_m_tile(env, R_hint, E, 32))
                 return launch_grouped<GateUpTinyS>(env, x_perm, W1, W3, H, offsets, row_index, index_div, R, E, f, d, s);
@@ -239,6 +252,16 @@ int launch_down_as(const GemmEnv& env, const moe_bf16* H, const int32_t* offsets
             if (single_m_tile(env, R_hint, E, 128))
                 return launch_grouped<Out<F32, DownMidS>>(env, H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
             return launch_grouped<Out<F32, DownMid>>(env, H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
+        case 4:
+            // wide tiles where there are enough of them for the 256 compute units, as for case 1
+            if (wide_mid) {
+                if (single_m_tile(env, R_hint, E, 96))
+                    return launch_grouped<Out<F32, DownMid96WideS>>(env, H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
+                return launch_grouped<Out<F32, DownMid96Wide>>(env, H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
+            }
+            if (single_m_tile(env, R_hint, E, 96))
+                return launch_grouped<Out<F32, DownMid96S>>(env, H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
+            return launch_grouped<Out<F32, DownMid96>>(env, H, W2, nullptr, y_perm, offsets, nullptr, 1, R, E, d, f, s);
         case 3:
             // with fewer routed rows than experts only about R experts have a tile: narrower
             // tiles so that their weights still stream through most compute units

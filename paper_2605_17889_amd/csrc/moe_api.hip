@@ -527,7 +527,7 @@ int moe_profile_end_per_call(moe_ctx* c, double* per_call_ms, int32_t capacity_c
 }
 
 /* Tuning/testing knob of one context: force the expert-GEMM tile configuration (0 large, 1 medium,
- * 2 small, 3 tiny rows-per-expert), or -1 for the automatic choice; +16 never loads weights as
+ * 2 small, 3 tiny rows-per-expert, 4 the 96-row medium tile), or -1 for the automatic choice; +16 never loads weights as
  * non-temporal, +32 always does (medium and small tiles); +64 makes the layer calls write the
  * gathered rows to the workspace instead of reading them through the permutation; +128 keeps the
  * large tiles of a last, partial round whole; +256 / +512 run the large tiles with eight / four
@@ -543,7 +543,7 @@ int moe_set_gemm_config(moe_ctx* c, int config) {
     if (config >= 63) { materialise = true; config -= 64; }
     if (config >= 31) { stream_mode = 1; config -= 32; }
     else if (config >= 15) { stream_mode = 0; config -= 16; }
-    if (config < -1 || config > 3) return MOE_ERR_INVALID_ARG;
+    if (config < -1 || config > 4) return MOE_ERR_INVALID_ARG;
     c->gemm.materialise_gather = materialise;
     c->gemm.split_last_round = split;
     c->gemm.large_tile_waves = large_waves;

@@ -279,7 +279,7 @@ def test_permute_bit_exact(T, E, k, seed, empty):
 
 
 # ---------------------------------------------------------------- expert FFN and combine
-@pytest.mark.parametrize("config", [0, 0 + 128, 0 + 256, 0 + 512, 1, 2, 3, 2 + 16, 3 + 32])   # +16 / +32: cached / non-temporal weights
+@pytest.mark.parametrize("config", [0, 0 + 128, 0 + 256, 0 + 512, 1, 2, 3, 4, 2 + 16, 3 + 32, 4 + 16, 4 + 32])   # +16 / +32: cached / non-temporal weights
 @pytest.mark.parametrize("d,f,rows", [
     (512, 256, [300, 0, 1, 77]),          # empty expert, single row, ragged tails
     (512, 512, [256, 257, 64, 31, 0, 5, 128, 129]),
@@ -311,7 +311,7 @@ def test_expert_ffn_parity(config, d, f, rows):
     ctx.close()
 
 
-ALL_TILE_CONFIGS = [0 + 256, 0 + 512, 1, 2, 3]
+ALL_TILE_CONFIGS = [0 + 256, 0 + 512, 1, 2, 3, 4]
 
 
 @pytest.mark.parametrize("config", ALL_TILE_CONFIGS)
@@ -508,10 +508,10 @@ def test_layer_tiny_ragged_T(T):
 def test_gemm_config_values():
     """The tuning knob belongs to one context and validates its argument."""
     ctx = B.MoeContext(16, 512, 256, 8, 2)
-    for bad in (9, 4 + 32, 4 + 64, 4 + 128, 4 + 256, 4 + 512, -2):
+    for bad in (9, 5, 5 + 32, 5 + 64, 5 + 128, 5 + 256, 5 + 512, -2):
         with pytest.raises(B.MoeError):
             B.moe_set_gemm_config(ctx, bad)
-    for ok in (0, 3, 1 + 16, -1 + 32, -1 + 64, 2 + 32 + 64, -1 + 128, 0 + 128 + 64, -1 + 256, -1 + 512, 0 + 512 + 128 + 64, -1):
+    for ok in (0, 3, 4, 4 + 32, 1 + 16, -1 + 32, -1 + 64, 2 + 32 + 64, -1 + 128, 0 + 128 + 64, -1 + 256, -1 + 512, 0 + 512 + 128 + 64, -1):
         B.moe_set_gemm_config(ctx, ok)
     ctx.close()
 
