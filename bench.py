@@ -36,7 +36,7 @@ NOMINAL_SCLK_MHZ = 2400.0       # the shader clock the published peaks are quote
 # and it describes the library as it was when that file was written. Other runs report null.
 RECORDED_TRAFFIC = {
     # (workload, micro_tokens): (bytes per gate/up launch, profile file)
-    ("mixtral8x22b_prefill", None): (11.65e9, "profiles/expert_gemm_mixtral8x22b_prefill_hbm_traffic.md"),
+    ("mixtral8x22b_prefill", None): (11.68e9, "profiles/expert_gemm_mixtral8x22b_prefill_hbm_traffic.md"),
     ("mixtral8x22b_coalesce", 256): (3.244e9, "profiles/microbatched_mixtral8x22b_hbm_traffic.md"),
 }
 
