@@ -41,6 +41,13 @@ RECORDED_TRAFFIC = {
 }
 
 
+# The driver refreshes the sysfs clock and power readings only every few tens of milliseconds and
+# they trail the load: over a timed region of 40 ms the medians came out at 1.0-1.7 GHz for work
+# that, repeated for 2.4 s at the same time per step, shows 2.0 GHz. Shorter regions than this
+# report no clock, no power and no clock-relative fraction.
+MIN_SAMPLED_SECONDS = 0.25
+
+
 class ClockSampler:
     """Shader clock and board power while the timed region runs, read from the amdgpu sysfs files
     (no tool is spawned): medians of the samples, so that the fraction of the peak AT THE CLOCK
@@ -437,6 +444,8 @@ def main():
         torch.cuda.synchronize()
         elapsed = time.perf_counter() - t0
         sclk_mhz, board_w = clock.stop()
+        if elapsed < MIN_SAMPLED_SECONDS:    # the sysfs readings trail the load: see the constant
+            sclk_mhz = board_w = None
         per_call, launches, calls = B.moe_profile_end_per_call(ctx, args.steps)
         stage_ms = {name: sum(c[name] for c in per_call) for name in B.STAGES}
     counts = torch.empty(cfg.E, dtype=torch.int32, device="cuda")
